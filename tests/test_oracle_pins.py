@@ -1,0 +1,341 @@
+"""Pins for the CPU oracle: closed forms, brute force, invariants and the values the paper
+prints.  None of these re-types an oracle formula: each compares against an independent
+fact, chosen so that a dropped term, wrong sign/index or transposed operand fails."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import locmoe_oracle as orc
+from paper_2401_13920_amd import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def golden():
+    vals = {}
+    with open(os.path.join(HERE, "golden", "paper_values.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                vals[line[0]] = float(line[1])
+    return vals
+
+
+# ------------------------------------------------------------------ capacity
+def test_p_delta_closed_form_d3():
+    # Archimedes: one coordinate of a uniform point on S^2 is uniform on [-1,1]
+    for delta in (0.0, 0.1, 0.37, 0.9, 1.0):
+        assert orc.p_delta(3, delta) == pytest.approx(1.0 - delta, abs=1e-12)
+
+
+def test_p_delta_closed_form_d2():
+    for delta in (0.05, 0.5, 0.99):
+        assert orc.p_delta(2, delta) == pytest.approx(2.0 / math.pi * math.acos(delta), abs=1e-12)
+
+
+def test_p_delta_monte_carlo():
+    rng = np.random.default_rng(7)
+    d = 24
+    u = rng.standard_normal((400000, d))
+    c = np.abs(u[:, 0]) / np.linalg.norm(u, axis=1)
+    for delta in (0.1, 0.25, 0.4):
+        emp = float(np.mean(c >= delta))
+        assert orc.p_delta(d, delta) == pytest.approx(emp, abs=4.0 * math.sqrt(emp * (1 - emp) / len(c)) + 1e-4)
+
+
+def test_p_delta_paper_worked_value():
+    g = golden()
+    lim = 1.0 - math.erf(math.sqrt(2.0) / 2.0)
+    assert round(math.erf(math.sqrt(2.0) / 2.0), 2) == g["erf_sqrt2_over_2"]
+    for d in (128, 1024, 4096):
+        p = orc.p_delta(d, math.sqrt(1.0 / (d - 1.5)))
+        assert round(p, 1) == g["p_delta_at_inv_sqrt_d"]
+        assert abs(p - lim) < 2.0 / d + 1e-4          # converges to 1 - erf(sqrt(2)/2)
+    assert orc.p_delta(4096, 3.0 / math.sqrt(4096)) < 0.01   # "declines to 0 rapidly"
+
+
+def test_theorem1_ordering_and_forms():
+    for (E, d, delta) in [(8, 128, 0.251), (16, 1024, 0.1142), (64, 4096, 0.065), (16, 1024, 0.03)]:
+        exact = orc.ec_min(E, d, delta, "exact")
+        erfc = orc.ec_min(E, d, delta, "erfc")
+        ex = orc.ec_min(E, d, delta, "exp")
+        assert erfc > ex                                   # the theorem's strict inequality
+        assert erfc == pytest.approx(exact, rel=0.07)      # large-d approximation
+        y = delta * delta * d / (2 - delta * delta)
+        assert ex * E == pytest.approx(math.exp(y))
+    # the approximation tightens as d grows
+    assert orc.ec_min(64, 4096, 0.065, "erfc") == pytest.approx(orc.ec_min(64, 4096, 0.065, "exact"), rel=0.005)
+
+
+def test_ec_min_scales_inverse_with_experts():
+    assert orc.ec_min(8, 256, 0.1, "exact") == pytest.approx(2 * orc.ec_min(16, 256, 0.1, "exact"))
+
+
+def test_capacity_table():
+    # the benchmark deltas reproduce the capacities of the five workloads
+    for c in wl.CONFIGS.values():
+        assert orc.capacity(c.T, c.E, c.d, 0.0, c.delta) == c.C
+        # the paper's measured delta makes the bound degenerate (less than one token)
+        assert orc.ec_min(c.E, c.d, wl.PAPER_DELTA, "erfc") < 1.0
+        assert orc.capacity(c.T, c.E, c.d, 0.0, wl.PAPER_DELTA) == 1
+    c3 = wl.CONFIGS[3]
+    assert [orc.capacity(c3.T, c3.E, c3.d, cf, c3.delta) for cf in (1.0, 1.25, 2.0)] == [1024, 1280, 2048]
+    assert orc.capacity(100, 8, 64, 0.0, 0.999) == 100     # clamped to T
+    assert orc.capacity(100, 8, 64, 1.0, 0.01) == 13       # ceil(100/8)
+
+
+# ------------------------------------------------------------------ gate
+def test_grap_weight_orthogonal_equal_norm():
+    for E, d in [(8, 128), (16, 1024), (128, 5120), (3, 21)]:
+        W = orc.grap_weight(E, d)
+        assert np.allclose(W @ W.T, (E / d) * np.eye(E), atol=1e-15)
+        assert np.allclose(W.sum(axis=1), 1.0)
+        assert np.count_nonzero(W) == d
+
+
+def test_gate_equals_dense_layer():
+    rng = np.random.default_rng(3)
+    for E, d in [(8, 128), (6, 48), (128, 5120)]:
+        x = rng.standard_normal((17, d))
+        assert np.allclose(orc.gate(x, E), orc.gate_dense(x, E), rtol=0, atol=1e-12)
+
+
+def test_gate_special_inputs():
+    E, d = 8, 64
+    assert np.allclose(orc.gate(np.full((2, d), 3.25), E), 3.25)
+    x = np.zeros((1, d)); x[0, 3 * 8:4 * 8] = 2.0           # one block set
+    g = orc.gate(x, E)
+    assert g[0, 3] == 2.0 and np.count_nonzero(g) == 1
+    x = np.zeros((1, d)); x[0, 8] = 8.0                      # first element of block 1
+    assert orc.gate(x, E)[0].tolist() == [0, 1.0, 0, 0, 0, 0, 0, 0]
+    with pytest.raises(ValueError):
+        orc.gate(np.zeros((1, 10)), 3)
+
+
+# ------------------------------------------------------------------ route
+def test_route_bruteforce_and_ties():
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal((300, 12)).astype(np.float32)
+    g[5] = -1.0                       # all clipped by ReLU -> all tie at 0 -> expert 0, w = 1/E
+    g[6, 3] = g[6, 9] = 7.0           # exact tie -> lowest id
+    eid, w, p, G = orc.route(g)
+    for m in range(300):
+        best, bi = -1.0, -1
+        for i in range(12):
+            v = max(float(g[m, i]), 0.0)
+            if v > best:
+                best, bi = v, i
+        assert eid[m] == bi
+    assert eid[5] == 0 and w[5] == pytest.approx(1.0 / 12)
+    assert eid[6] == 3
+    assert np.allclose(p.sum(axis=1), 1.0)
+    assert np.all(w >= 1.0 / 12 - 1e-15)
+    assert np.all(w == p.max(axis=1))
+
+
+def test_route_softmax_hand_value():
+    g = np.array([[0.0, math.log(3.0), -5.0]], dtype=np.float32)
+    eid, w, p, _ = orc.route(g)
+    # ReLU zeroes the last one: exp -> 1, 3, 1
+    assert eid[0] == 1
+    assert p[0] == pytest.approx([0.2, 0.6, 0.2], rel=1e-6)
+    eid, w, p, _ = orc.route(g, eps=np.array([2.0, 0.0, 0.0], np.float32))
+    assert eid[0] == 0
+    eid, w, p, _ = orc.route(g, relu=False)
+    assert p[0, 2] == pytest.approx(math.exp(-5) / (1 + 3 + math.exp(-5)), rel=1e-6)
+
+
+def test_lemma1_min_angle_expert():
+    # equal-norm gating weights: the chosen expert has the largest cosine to omega_i
+    c = wl.CONFIGS[1]
+    x, _ = wl.hidden_states(c)
+    W = orc.grap_weight(c.E, c.d)
+    g = orc.gate(x, c.E)
+    eid, _, _, _ = orc.route(g.astype(np.float32))
+    cos = (x.astype(np.float64) @ W.T) / (np.linalg.norm(x, axis=1)[:, None] * np.linalg.norm(W, axis=1)[None, :])
+    pos = g.max(axis=1) > 1e-6
+    assert pos.sum() > 100
+    assert np.array_equal(eid[pos], np.argmax(cos, axis=1)[pos])
+
+
+def test_lemma2_uniform_sphere_equal_probability():
+    rng = np.random.default_rng(11)
+    E, d, T = 8, 64, 40000
+    u = rng.standard_normal((T, d)); u /= np.linalg.norm(u, axis=1, keepdims=True)
+    eid, _, _, _ = orc.route(orc.gate(u, E).astype(np.float32))
+    cnt = np.bincount(eid, minlength=E)
+    chi2 = float(((cnt - T / E) ** 2 / (T / E)).sum())
+    assert chi2 < 24.3        # chi-square, 7 dof, p = 0.001
+
+
+# ------------------------------------------------------------------ losses
+def test_aux_loss_extremes():
+    g = golden()
+    E, T = 8, 64
+    eid = (np.arange(T) % E).astype(np.int32)
+    p = np.full((T, E), 1.0 / E)
+    assert orc.route_stats(eid, p, None, None, 0, alpha=g["alpha"])["L_aux"] == pytest.approx(g["alpha"])
+    eid = np.zeros(T, np.int32)
+    p = np.zeros((T, E)); p[:, 0] = 1.0
+    assert orc.route_stats(eid, p, None, None, 0, alpha=g["alpha"])["L_aux"] == pytest.approx(g["alpha"] * E)
+
+
+def test_locality_kl_hand_example():
+    # 2 nodes x 2 experts, 8 tokens: homes 6/2 -> D_l = (3/8,3/8,1/8,1/8)
+    e2n = np.array([0, 0, 1, 1]); home = np.array([0, 0, 0, 0, 0, 0, 1, 1])
+    eid = np.array([0, 0, 0, 0, 1, 1, 2, 3], np.int32)       # f = (1/2,1/4,1/8,1/8)
+    p = np.full((8, 4), 0.25)
+    s = orc.route_stats(eid, p, home, e2n, 2, mu=0.5)
+    expect = 0.5 * math.log(0.5 / 0.375) + 0.25 * math.log(0.25 / 0.375)
+    assert s["KL_hard"] == pytest.approx(expect, rel=1e-12)
+    assert s["L_loc"] == pytest.approx(0.5 * expect, rel=1e-12)
+    assert s["KL_soft"] == pytest.approx(2 * 0.25 * math.log(0.25 / 0.375) + 2 * 0.25 * math.log(0.25 / 0.125))
+    assert s["locality_frac"] == pytest.approx(1.0)
+    # assignment exactly proportional to the localized distribution -> KL = 0
+    eid = np.array([0, 0, 0, 1, 1, 1, 2, 3], np.int32)
+    assert orc.route_stats(eid, p, home, e2n, 2)["KL_hard"] == pytest.approx(0.0, abs=1e-15)
+    # KL >= 0 on random assignments; empty experts contribute 0 ln 0 = 0
+    rng = np.random.default_rng(2)
+    for _ in range(20):
+        eid = rng.integers(0, 4, 8).astype(np.int32)
+        assert orc.route_stats(eid, p, home, e2n, 2)["KL_hard"] >= -1e-15
+    # a node with no home tokens but assigned tokens -> +inf
+    s = orc.route_stats(np.array([2, 2], np.int32), np.full((2, 4), 0.25), np.array([0, 0]), e2n, 2)
+    assert math.isinf(s["KL_hard"])
+    assert s["locality_frac"] == 0.0
+
+
+# ------------------------------------------------------------------ slots / dispatch
+def _check_slot_invariants(eid, E, C, e2n, N, s):
+    T = len(eid)
+    cnt = np.bincount(eid, minlength=E)
+    assert cnt.sum() == T
+    assert np.array_equal(s["cnt"], cnt)
+    assert np.array_equal(s["kept"], np.minimum(cnt, C))
+    K = int(s["seg_off"][-1])
+    assert K == s["kept"].sum() and K + int((s["slot"] < 0).sum()) == T
+    kept_slots = np.sort(s["slot"][s["slot"] >= 0])
+    assert np.array_equal(kept_slots, np.arange(K))                     # bijection onto [0,K)
+    order = s["buf_expert"]
+    keys = [(int(e2n[e]), int(e)) for e in order]
+    assert keys == sorted(keys) and sorted(order.tolist()) == list(range(E))
+    for r, e in enumerate(order):
+        rows = s["row_token"][s["seg_off"][r]:s["seg_off"][r + 1]]
+        assert np.all(np.diff(rows) > 0)                                  # stable: token order
+        assert np.all(eid[rows] == e)
+        first = np.nonzero(eid == e)[0][:C]
+        assert np.array_equal(rows, first)                                # first-come kept
+    for nu in range(N):
+        a, b = s["node_off"][nu], s["node_off"][nu + 1]
+        assert np.all(e2n[eid[s["row_token"][a:b]]] == nu)
+    assert s["node_off"][-1] == K
+
+
+def test_slots_bruteforce_config1():
+    c = wl.CONFIGS[1]
+    x, home = wl.hidden_states(c)
+    eid, _, _, _ = orc.route(orc.gate(x, c.E).astype(np.float32))
+    e2n = wl.expert_to_node(c)
+    for C in (1, c.C, 64, c.T):
+        s = orc.slots(eid, c.E, C, e2n, c.N)
+        assert np.array_equal(s["pos"], orc.pos_bruteforce(eid))
+        _check_slot_invariants(eid, c.E, C, e2n, c.N, s)
+        if C >= np.bincount(eid, minlength=c.E).max():
+            assert np.all(s["slot"] >= 0)
+        if C == 1:
+            present = np.unique(eid)
+            assert int(s["seg_off"][-1]) == len(present)
+            assert set(s["row_token"].tolist()) == {int(np.nonzero(eid == e)[0][0]) for e in present}
+
+
+def test_slots_permuted_node_map_and_empty_experts():
+    rng = np.random.default_rng(9)
+    E, N, T, C = 10, 3, 500, 40
+    eid = rng.choice([0, 1, 2, 4, 7, 9], size=T, p=[.4, .3, .1, .1, .05, .05]).astype(np.int32)
+    e2n = np.array([2, 0, 1, 1, 0, 2, 2, 0, 1, 0], np.int32)
+    s = orc.slots(eid, E, C, e2n, N)
+    _check_slot_invariants(eid, E, C, e2n, N, s)
+    assert s["buf_expert"].tolist() == [1, 4, 7, 9, 2, 3, 8, 0, 5, 6]
+    assert s["kept"][3] == 0 and s["kept"][0] == C
+
+
+def test_dispatch_combine_round_trip():
+    c = wl.small_config()
+    x, home = wl.hidden_states(c)
+    e2n = wl.expert_to_node(c)
+    eid, w, _, _ = orc.route(orc.gate(x, c.E).astype(np.float32))
+    s = orc.slots(eid, c.E, 9, e2n, c.N)
+    K = int(s["seg_off"][-1])
+    send = orc.dispatch(x, s["slot"], K)
+    assert np.array_equal(send, x[s["row_token"]])
+    y = orc.combine(send.astype(np.float64), s["slot"], np.ones(c.T))
+    keptm = s["slot"] >= 0
+    assert np.array_equal(y[keptm], x[keptm].astype(np.float64))
+    assert np.all(y[~keptm] == 0) and (~keptm).any()
+
+
+# ------------------------------------------------------------------ FFN / combine
+def test_gelu_facts():
+    assert orc.gelu(np.array([0.0]))[0] == 0.0
+    assert orc.gelu(np.array([10.0]))[0] == pytest.approx(10.0, rel=1e-12)
+    assert orc.gelu(np.array([-10.0]))[0] == pytest.approx(0.0, abs=1e-12)
+    assert orc.gelu(np.array([1.0]))[0] == pytest.approx(0.8413447460685429, rel=1e-12)   # Phi(1)
+    v = np.linspace(-4, 4, 33)
+    assert np.allclose(orc.gelu(v) - orc.gelu(-v), v)        # x Phi(x) + x Phi(-x) ... = x
+
+
+def test_ffn_against_loops_config1():
+    c = wl.CONFIGS[1]
+    x, _ = wl.hidden_states(c, 6)
+    W_in, W_out = wl.expert_weights(c, 2)
+    a = orc.ffn_rows(x, W_in, W_out)
+    b = orc.ffn_rows_loops(x, W_in, W_out)
+    assert np.allclose(a, b, rtol=1e-11, atol=1e-14)
+
+
+def test_ffn_closed_forms():
+    rng = np.random.default_rng(4)
+    d, h = 6, 9
+    S = rng.standard_normal((5, d))
+    W_in = np.zeros((d, h)); W_in[:, :d] = np.eye(d)          # [I 0]
+    W_out = np.zeros((h, d)); W_out[:d, :] = 2.0 * np.eye(d)
+    assert np.allclose(orc.ffn_rows(S, W_in, W_out), 2.0 * orc.gelu(S), atol=1e-15)
+    assert np.all(orc.ffn_rows(S, np.zeros((d, h)), rng.standard_normal((h, d))) == 0.0)
+    # non-square, asymmetric: a transposed operand would not even have this value
+    W_in = rng.standard_normal((d, h)); W_out = rng.standard_normal((h, d))
+    ref = np.stack([sum(orc.gelu(np.array([S[r] @ W_in[:, j]]))[0] * W_out[j] for j in range(h)) for r in range(5)])
+    assert np.allclose(orc.ffn_rows(S, W_in, W_out), ref, atol=1e-12)
+
+
+def test_moe_layer_one_term_per_token():
+    c = wl.small_config(dtype="f32")
+    x, home = wl.hidden_states(c)
+    e2n = wl.expert_to_node(c)
+    ws = {e: wl.expert_weights(c, e) for e in range(c.E)}
+    r = orc.moe_layer(x, home, e2n, c.E, c.N, 9, lambda e: ws[e])
+    # Eq. 1 by its definition, token by token
+    for m in range(c.T):
+        e = int(np.argmax(np.maximum(r["g32"][m], 0)))
+        if r["slot"][m] < 0:
+            assert np.all(r["y"][m] == 0)
+            continue
+        G = np.maximum(r["g32"][m].astype(np.float64), 0)
+        score = math.exp(G[e]) / np.exp(G).sum()
+        ref = score * (orc.gelu(x[m].astype(np.float64) @ ws[e][0].astype(np.float64)) @ ws[e][1].astype(np.float64))
+        assert np.allclose(r["y"][m], ref, rtol=1e-10, atol=1e-14)
+    assert (r["slot"] < 0).any()
+
+
+# ------------------------------------------------------------------ input generators
+def test_workloads_are_seeded_and_representable():
+    c = wl.CONFIGS[2]
+    x1, h1 = wl.hidden_states(c, 64)
+    x2, h2 = wl.hidden_states(c, 64)
+    assert np.array_equal(x1, x2) and np.array_equal(h1, h2)
+    assert np.array_equal(wl.round_to_storage(x1, "bf16"), x1)
+    assert set(h1[:c.N].tolist()) == set(range(c.N))
+    # bf16 rounding is round-to-nearest-even
+    a = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7, -1.0 - 2 ** -8 - 2 ** -20], np.float32)
+    assert wl.round_to_storage(a, "bf16").tolist() == [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7, -1.0 - 2 ** -7]
