@@ -223,28 +223,28 @@ def gelu(v: np.ndarray) -> np.ndarray:
 
 
 def ffn_rows(S: np.ndarray, W_in: np.ndarray, W_out: np.ndarray) -> np.ndarray:
-    """One expert on its rows: W_out . GeLU(W_in . x), with W_in stored [d,h] and W_out
-    [h,d] so that rows multiply from the left.  No biases, no intermediate rounding."""
-    H = gelu(np.asarray(S, dtype=np.float64) @ np.asarray(W_in, dtype=np.float64))
-    return H @ np.asarray(W_out, dtype=np.float64)
+    """One expert on its rows: W_out . GeLU(W_in . x) with Eq. 1's orientation, W_in [h,d]
+    and W_out [d,h]; the rows of S are the x vectors.  No biases, no intermediate rounding."""
+    H = gelu(np.asarray(S, dtype=np.float64) @ np.asarray(W_in, dtype=np.float64).T)
+    return H @ np.asarray(W_out, dtype=np.float64).T
 
 
 def ffn_rows_loops(S, W_in, W_out) -> np.ndarray:
     """Triple-loop twin of :func:`ffn_rows` for tiny shapes."""
     R, d = S.shape
-    h = W_in.shape[1]
-    O = np.zeros((R, W_out.shape[1]), dtype=np.float64)
+    h = W_in.shape[0]
+    O = np.zeros((R, W_out.shape[0]), dtype=np.float64)
     for r in range(R):
         hid = [0.0] * h
         for j in range(h):
             a = 0.0
             for k in range(d):
-                a += float(S[r, k]) * float(W_in[k, j])
+                a += float(W_in[j, k]) * float(S[r, k])
             hid[j] = a * 0.5 * (1.0 + math.erf(a / math.sqrt(2.0)))
-        for c in range(W_out.shape[1]):
+        for c in range(W_out.shape[0]):
             a = 0.0
             for j in range(h):
-                a += hid[j] * float(W_out[j, c])
+                a += float(W_out[c, j]) * hid[j]
             O[r, c] = a
     return O
 

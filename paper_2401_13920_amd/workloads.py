@@ -158,13 +158,15 @@ def expert_to_node(c: Config) -> np.ndarray:
 # expert weights: always bf16 storage, one expert at a time
 # ----------------------------------------------------------------------------
 def expert_weights_bits(c: Config, e: int):
-    """(W_in [d,h], W_out [h,d]) of expert e as uint16 bf16 bit patterns; iid N(0, 0.02^2)."""
+    """(W_in [h,d], W_out [d,h]) of expert e as uint16 bf16 bit patterns; iid N(0, 0.02^2).
+    Orientation is Eq. 1's: W_in maps a hidden vector to the inner width (W_in . x), W_out
+    maps back, both stored row-major."""
     rng = _rng(c.cfg, 10 + e)
-    w_in = rng.standard_normal((c.d, c.h), dtype=np.float32)
+    w_in = rng.standard_normal((c.h, c.d), dtype=np.float32)
     w_in *= np.float32(0.02)
     b_in = f32_to_bf16_bits(w_in)
     del w_in
-    w_out = rng.standard_normal((c.h, c.d), dtype=np.float32)
+    w_out = rng.standard_normal((c.d, c.h), dtype=np.float32)
     w_out *= np.float32(0.02)
     b_out = f32_to_bf16_bits(w_out)
     return b_in, b_out

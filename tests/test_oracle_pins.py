@@ -299,13 +299,13 @@ def test_ffn_closed_forms():
     rng = np.random.default_rng(4)
     d, h = 6, 9
     S = rng.standard_normal((5, d))
-    W_in = np.zeros((d, h)); W_in[:, :d] = np.eye(d)          # [I 0]
-    W_out = np.zeros((h, d)); W_out[:d, :] = 2.0 * np.eye(d)
+    W_in = np.zeros((h, d)); W_in[:d, :] = np.eye(d)          # [I; 0]
+    W_out = np.zeros((d, h)); W_out[:, :d] = 2.0 * np.eye(d)
     assert np.allclose(orc.ffn_rows(S, W_in, W_out), 2.0 * orc.gelu(S), atol=1e-15)
-    assert np.all(orc.ffn_rows(S, np.zeros((d, h)), rng.standard_normal((h, d))) == 0.0)
-    # non-square, asymmetric: a transposed operand would not even have this value
-    W_in = rng.standard_normal((d, h)); W_out = rng.standard_normal((h, d))
-    ref = np.stack([sum(orc.gelu(np.array([S[r] @ W_in[:, j]]))[0] * W_out[j] for j in range(h)) for r in range(5)])
+    assert np.all(orc.ffn_rows(S, np.zeros((h, d)), rng.standard_normal((d, h))) == 0.0)
+    # non-square, asymmetric: Eq. 1 column by column, W_out . GeLU(W_in . x)
+    W_in = rng.standard_normal((h, d)); W_out = rng.standard_normal((d, h))
+    ref = np.stack([sum(orc.gelu(np.array([W_in[j] @ S[r]]))[0] * W_out[:, j] for j in range(h)) for r in range(5)])
     assert np.allclose(orc.ffn_rows(S, W_in, W_out), ref, atol=1e-12)
 
 
@@ -323,7 +323,7 @@ def test_moe_layer_one_term_per_token():
             continue
         G = np.maximum(r["g32"][m].astype(np.float64), 0)
         score = math.exp(G[e]) / np.exp(G).sum()
-        ref = score * (orc.gelu(x[m].astype(np.float64) @ ws[e][0].astype(np.float64)) @ ws[e][1].astype(np.float64))
+        ref = score * (ws[e][1].astype(np.float64) @ orc.gelu(ws[e][0].astype(np.float64) @ x[m].astype(np.float64)))
         assert np.allclose(r["y"][m], ref, rtol=1e-10, atol=1e-14)
     assert (r["slot"] < 0).any()
 
