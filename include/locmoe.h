@@ -1,0 +1,149 @@
+/*
+ * locmoe.h - C ABI of the MI355X (gfx950) forward hot path of one LocMoE mixture-of-experts
+ * layer (arXiv 2401.13920, Section 3.2) on one GPU's share of the tokens:
+ *
+ *   GrAP gate -> top-1 route (+ auxiliary / locality terms) -> capacity-bounded stable
+ *   dispatch into a node-grouped send buffer -> expert FFN (grouped GEMM) -> combine.
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross the boundary.  Every function returns an int status:
+ *     LOCMOE_OK (0) or a negative LOCMOE_ERR_* code; locmoe_status_string() names it.
+ *   - All arguments are validated on the host before anything is launched, so the error
+ *     paths work without a GPU.
+ *   - "device" pointers are HIP device memory, 16-byte aligned, rows contiguous.  The caller
+ *     owns every buffer; the library allocates nothing and keeps no state between calls.
+ *   - Device functions only enqueue kernels on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and return; the caller synchronises.
+ *   - Notation (the paper's where it has one): T tokens, d hidden size, E experts (the
+ *     paper's n), N simulated nodes, h FFN inner width, C expert capacity in rows,
+ *     cnt[e] tokens whose top-1 expert is e, kept[e] = min(cnt[e], C), K = sum kept[e].
+ *   - Shape limits: d % E == 0; E % N == 0 is NOT required (e2n is free-form);
+ *     d % 8 == 0 and h % 8 == 0 (16-byte rows); 1 <= E <= 1024; 1 <= N <= E;
+ *     T*max(d,h) element offsets must fit in 63 bits and T, E*C in 31 bits.
+ */
+#ifndef LOCMOE_H
+#define LOCMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  LOCMOE_OK = 0,
+  LOCMOE_ERR_NULL = -1,      /* a required pointer is NULL */
+  LOCMOE_ERR_SHAPE = -2,     /* a size is < 1 or breaks a divisibility / range limit above */
+  LOCMOE_ERR_ARG = -3,       /* bad dtype / flag / delta / capacity-factor value */
+  LOCMOE_ERR_WORKSPACE = -4, /* workspace pointer NULL or smaller than locmoe_workspace_bytes */
+  LOCMOE_ERR_HIP = -5        /* a HIP launch failed (hipGetLastError was not hipSuccess) */
+};
+
+enum { LOCMOE_F32 = 0, LOCMOE_BF16 = 1 };
+
+/* Shape of one MoE layer call.  x_dtype is the storage type of x, send, out and y; expert
+ * weights and the FFN intermediate are always bf16; gating values and scores are fp32. */
+typedef struct locmoe_desc {
+  int32_t T, d, E, N, h, C;
+  int32_t x_dtype; /* LOCMOE_F32 or LOCMOE_BF16 */
+  int32_t relu;    /* 1: G = ReLU(g + eps) as printed below Eq. 3; 0: G = g + eps */
+  float alpha;     /* auxiliary-loss weight of Eq. 5 (the paper uses 0.01) */
+  float mu;        /* locality-loss weight of Eq. 6 (left open by the paper) */
+} locmoe_desc;
+
+const char* locmoe_status_string(int status);
+
+/* ---- host-only scalars (Section 3.2.3) ------------------------------------------------ */
+
+/* Theorem 1: lower bound of the expert capacity, in tokens, from the cosine threshold delta of
+ * Assumption 3.  form 0: 1/(E*p_delta) with Lemma 3's p_delta = 1 - I_{delta^2}(1/2,(d-1)/2);
+ * form 1: the large-d form 1/(E*erfc(sqrt(y))); form 2: exp(y)/E; y = delta^2 d/(2-delta^2).
+ * Host pointers.  *ec_min may be +inf.  Errors: NULL, E<1, d<2, delta outside (0,1), form. */
+int locmoe_capacity_min(int32_t E, int32_t d, double delta, int32_t form, double* ec_min);
+
+/* Lemma 3: *p = 1 - I_{delta^2}(1/2,(d-1)/2).  Host pointer.  delta in [0,1], d >= 2. */
+int locmoe_p_delta(int32_t d, double delta, double* p);
+
+/* Capacity in rows per expert: the empirical capacity of Section 3.2.3 on one device's share,
+ * ceil(cf*T/E), floored by ceil of the Theorem 1 bound (form 1) and clamped to [1,T].
+ * cf == 0 selects the bound alone.  Host pointer.  Errors: NULL, sizes < 1, cf < 0, delta. */
+int locmoe_capacity(int32_t T, int32_t E, int32_t d, double cf, double delta, int32_t* C);
+
+/* Bytes of device scratch that locmoe_route and locmoe_dispatch need (one buffer serves
+ * both, they do not overlap in time on one stream).  0 on an invalid descriptor. */
+size_t locmoe_workspace_bytes(const locmoe_desc* desc);
+
+/* ---- device steps ---------------------------------------------------------------------- */
+
+/* GrAP gating value (Eq. 4 and the text below Eq. 3): g[m,i] = omega_i . x_m = mean of the
+ * i-th contiguous block of d/E features of token m, accumulated in fp32.  Raw value: the
+ * bias and the ReLU are applied by locmoe_route.
+ *   x  device [T,d] of x_dtype (read)      g  device [T,E] fp32 (written)              */
+int locmoe_gate(const locmoe_desc* desc, const void* x, float* g, void* stream);
+
+/* Top-1 routing (Eq. 2, Eq. 3) and the forward values of Eq. 5 and Eq. 6.
+ *   G = g + eps (eps NULL = 0), ReLU if desc->relu; eid[m] = lowest index attaining max_i G;
+ *   w[m] = softmax(G[m,:])[eid[m]]; cnt[e] = #{m: eid[m]=e}; Psum[e] = sum_m softmax(G[m,:])[e].
+ *   stats[0] L_aux = alpha*E*sum f_i P_i (f = cnt/T before any capacity drop, P = Psum/T)
+ *   stats[1] KL(f || D_l)   stats[2] KL(P || D_l)   stats[3] L_loc = mu*stats[1]
+ *   stats[4] fraction of tokens whose expert sits on their home node
+ *   stats[5] max_e cnt[e]   stats[6] number of experts with cnt = 0   stats[7] 0
+ *   D_l[i] = (#tokens whose home is node(i)) / (T * #experts on node(i)): every token spread
+ *   evenly over the experts of its home node.  0 ln 0 = 0; KL = +inf if D_l[i] = 0 < D_c[i].
+ *   home NULL: stats[1..4] = 0.
+ *   g device [T,E] fp32; eps device [E] fp32 or NULL; home device [T] i32 in [0,N) or NULL;
+ *   e2n device [E] i32 in [0,N) or NULL (= e / (E/N), which then needs E % N == 0);
+ *   eid device [T] i32, w device [T] fp32, cnt device [E] i32, Psum device [E] fp32,
+ *   stats device [8] fp32 (all written); ws device scratch of >= locmoe_workspace_bytes.
+ * Sums are formed in a fixed order (no floating-point atomics): results are deterministic. */
+int locmoe_route(const locmoe_desc* desc, const float* g, const float* eps, const int32_t* home,
+                 const int32_t* e2n, int32_t* eid, float* w, int32_t* cnt, float* Psum,
+                 float* stats, void* ws, size_t ws_bytes, void* stream);
+
+/* Capacity-bounded stable dispatch (capacity: Section 3.2.3; layout: this library's).
+ *   pos[m] = #{m' < m : eid[m'] = eid[m]}; token m is kept iff pos[m] < C (first come by token
+ *   index).  Experts are laid out in buffer order = sorted by (e2n[e], e); rank r holds expert
+ *   buf_expert[r] in rows [seg_off[r], seg_off[r+1]), kept[e] rows in token order; node nu owns
+ *   rows [node_off[nu], node_off[nu+1]).  slot[m] = seg_off[rank(eid[m])] + pos[m] or -1 when
+ *   dropped; row_token[slot[m]] = m; send[slot[m],:] = x[m,:] (bit copy).  K = seg_off[E].
+ *   x device [T,d]; eid device [T] i32 in [0,E); e2n as in locmoe_route;
+ *   written: pos [T], slot [T], kept [E], seg_off [E+1], node_off [N+1], buf_expert [E],
+ *   row_token [E*C] (first K valid), send [E*C,d] of x_dtype (first K rows valid; rows >= K
+ *   are left untouched).  ws as in locmoe_route.  Integer-only and independent of any
+ *   atomic arrival order: bit-identical from run to run. */
+int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n,
+                    int32_t* pos, int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off,
+                    int32_t* buf_expert, int32_t* row_token, void* send, void* ws, size_t ws_bytes,
+                    void* stream);
+
+/* Expert FFN of Eq. 1 as a grouped GEMM over the send buffer's segments:
+ *   out[r,:] = W_out[e] . GeLU(W_in[e] . send[r,:]) for r in segment of e = buf_expert[rank],
+ *   GeLU(v) = v*Phi(v) (erf form), no biases.  bf16 MFMA with fp32 accumulation; the
+ *   intermediate is rounded once to bf16 (H_ws), out once to x_dtype.
+ *   send device [E*C,d] of x_dtype; seg_off device [E+1]; buf_expert device [E];
+ *   W_in device [E,h,d] bf16 and W_out device [E,d,h] bf16, row-major in Eq. 1's orientation;
+ *   H_ws device [E*C,h] bf16 scratch; out device [E*C,d] of x_dtype (rows < K written).
+ *   The row count K is read on the device from seg_off: no host synchronisation. */
+int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                      const int32_t* buf_expert, const void* W_in, const void* W_out, void* H_ws,
+                      void* out, void* stream);
+
+/* The two linear transformations of Eq. 1 as separate launches (locmoe_expert_ffn is exactly
+ * _in followed by _out on the same stream); same buffers, layouts and errors as above.
+ *   _in :  H_ws[r,:] = GeLU(W_in[e] . send[r,:])  (bf16)      _out:  out[r,:] = W_out[e] . H_ws[r,:] */
+int locmoe_expert_ffn_in(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                         const int32_t* buf_expert, const void* W_in, void* H_ws, void* stream);
+int locmoe_expert_ffn_out(const locmoe_desc* desc, const void* H_ws, const int32_t* seg_off,
+                          const int32_t* buf_expert, const void* W_out, void* out, void* stream);
+
+/* Gate-weighted combine (Eq. 1 with the top-1 score of Eq. 3):
+ *   y[m,:] = w[m]*out[slot[m],:] if slot[m] >= 0 else 0; product in fp32, rounded to x_dtype.
+ *   out device [E*C,d]; slot device [T]; w device [T] fp32; y device [T,d] (every row written). */
+int locmoe_combine(const locmoe_desc* desc, const void* out, const int32_t* slot, const float* w,
+                   void* y, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOCMOE_H */

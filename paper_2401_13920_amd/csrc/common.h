@@ -1,0 +1,91 @@
+// Internal helpers shared by the gfx950 kernels of liblocmoe (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "locmoe.h"
+
+namespace locmoe {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// 16-byte streaming accesses (non-temporal hint: the data is touched once by this kernel)
+__device__ __forceinline__ uint4 nt_load16(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store16(const uint4& v, uint4* p) {
+  u32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, (u32x4*)p);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Round-to-nearest-even float -> bf16 bits (finite inputs); gfx950 has the conversion in hardware.
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(uint16_t, b);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+}
+
+// Sum of the 8 bf16 values held in a 16-byte vector, as a fixed fp32 tree.
+__device__ __forceinline__ float sum8_bf16(const uint4& v) {
+  float a0 = bf16_bits_to_f32(v.x & 0xFFFFu), a1 = __uint_as_float(v.x & 0xFFFF0000u);
+  float a2 = bf16_bits_to_f32(v.y & 0xFFFFu), a3 = __uint_as_float(v.y & 0xFFFF0000u);
+  float a4 = bf16_bits_to_f32(v.z & 0xFFFFu), a5 = __uint_as_float(v.z & 0xFFFF0000u);
+  float a6 = bf16_bits_to_f32(v.w & 0xFFFFu), a7 = __uint_as_float(v.w & 0xFFFF0000u);
+  return ((a0 + a1) + (a2 + a3)) + ((a4 + a5) + (a6 + a7));
+}
+__device__ __forceinline__ float sum4_f32(const uint4& v) {
+  return (__uint_as_float(v.x) + __uint_as_float(v.y)) + (__uint_as_float(v.z) + __uint_as_float(v.w));
+}
+
+// ---- cross-lane moves on the DPP path (no LDS traffic) ------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each group of 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each row of 16
+
+// All-reduce sum over aligned groups of L lanes (L a power of two <= 64): every lane of a
+// group ends with the group's total.  The steps below 16 lanes are DPP; 16 and 32 go through
+// the cross-lane permute unit.  The order of additions is fixed, so the result is deterministic.
+template <int L>
+__device__ __forceinline__ float group_sum(float v) {
+  if (L >= 2) v += dpp_f32<kDppXor1>(v);
+  if (L >= 4) v += dpp_f32<kDppXor2>(v);
+  if (L >= 8) v += dpp_f32<kDppHalfMirror>(v);
+  if (L >= 16) v += dpp_f32<kDppMirror>(v);
+  if (L >= 32) v += __shfl_xor(v, 16);
+  if (L >= 64) v += __shfl_xor(v, 32);
+  return v;
+}
+
+__host__ __device__ constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline int launch_status() { return hipGetLastError() == hipSuccess ? LOCMOE_OK : LOCMOE_ERR_HIP; }
+
+// host-side validation shared by the entry points
+int check_desc(const locmoe_desc* d);
+
+// route / dispatch scratch layout (see workspace.cpp)
+constexpr int kRouteMaxBlocks = 256;     // upper bound of route blocks (partials per block)
+constexpr int kDispatchTokensPerBlock = 1024;
+
+}  // namespace locmoe

@@ -1,0 +1,245 @@
+// Capacity-bounded stable dispatch (capacity: Section 3.2.3).
+//   1. dispatch_hist_kernel   per block of 1024 tokens: count of tokens per expert
+//   2. dispatch_slots_kernel  every block re-derives, from the [blocks,E] count matrix, the
+//      tokens before it per expert and the totals, hence kept[], the buffer order and the
+//      segment offsets; then ranks its own tokens (wave ballots + ordered wave prefixes)
+//   3. dispatch_copy_kernel   send[r,:] = x[row_token[r],:] for r < K, 16-byte vectors
+// Integer-only; LDS integer atomics appear only where the result does not depend on their
+// order, so slots are bit-identical from run to run.
+#include "common.h"
+
+namespace locmoe {
+namespace {
+
+constexpr int kDispThreads = 256;
+constexpr int kDispWaves = kDispThreads / kWave;
+constexpr int kTokPerWave = kDispatchTokensPerBlock / kDispWaves;  // contiguous tokens per wave
+constexpr int kIter = kTokPerWave / kWave;
+
+// Orders this wave's LDS accesses before the call against those after it, for all lanes.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kDispThreads) void dispatch_hist_kernel(const int32_t* __restrict__ eid,
+                                                                     int32_t* __restrict__ blockcnt, int T,
+                                                                     int E) {
+  extern __shared__ int32_t hist[];
+  for (int i = threadIdx.x; i < E; i += kDispThreads) hist[i] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kDispatchTokensPerBlock;
+#pragma unroll
+  for (int k = 0; k < kDispatchTokensPerBlock / kDispThreads; ++k) {
+    const int m = base + k * kDispThreads + threadIdx.x;
+    if (m < T) atomicAdd(&hist[eid[m]], 1);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < E; i += kDispThreads) blockcnt[(size_t)blockIdx.x * E + i] = hist[i];
+}
+
+// LDS layout of the slots kernel (ints): off[E] tot[E] node[E] rank[E] seg[E+1] wcnt[waves][E]
+__global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
+    const int32_t* __restrict__ eid, const int32_t* __restrict__ e2n, const int32_t* __restrict__ blockcnt,
+    int32_t* __restrict__ pos, int32_t* __restrict__ slot, int32_t* __restrict__ kept,
+    int32_t* __restrict__ seg_off, int32_t* __restrict__ node_off, int32_t* __restrict__ buf_expert,
+    int32_t* __restrict__ row_token, int T, int E, int N, int C, int nblocks, int nbits) {
+  extern __shared__ int32_t sm[];
+  int32_t* off = sm;
+  int32_t* tot = off + E;
+  int32_t* node = tot + E;
+  int32_t* rank = node + E;
+  int32_t* seg = rank + E;  // [E+1], indexed by buffer rank
+  int32_t* wcnt = seg + E + 1;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int b = blockIdx.x;
+
+  // tokens per expert in earlier blocks, and in all blocks
+  for (int e = tid; e < E; e += kDispThreads) {
+    int before = 0, all = 0;
+    for (int q = 0; q < nblocks; ++q) {
+      const int c = blockcnt[(size_t)q * E + e];
+      before += q < b ? c : 0;
+      all += c;
+    }
+    off[e] = before;
+    tot[e] = all < C ? all : C;  // kept[e] = min(cnt[e], C)
+    node[e] = e2n ? e2n[e] : e / (E / N);
+  }
+  for (int i = tid; i < kDispWaves * E; i += kDispThreads) wcnt[i] = 0;
+  __syncthreads();
+  // buffer order: experts sorted by (node, id)
+  for (int e = tid; e < E; e += kDispThreads) {
+    int r = e;
+    if (e2n) {
+      r = 0;
+      const int ne = node[e];
+      for (int q = 0; q < E; ++q) r += (node[q] < ne || (node[q] == ne && q < e)) ? 1 : 0;
+    }
+    rank[e] = r;
+    seg[r + 1] = tot[e];  // staged: kept of the expert at rank r, scanned below
+  }
+  __syncthreads();
+  if (wave == 0) {  // inclusive scan of seg[1..E] by one wave: lane owns a contiguous run
+    const int per = ceil_div(E, kWave);
+    const int lo = lane * per, hi = min(E, lo + per);
+    int s = 0;
+    for (int i = lo; i < hi; ++i) s += seg[i + 1];
+    int incl = s;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int o = __shfl_up(incl, d);
+      if (lane >= d) incl += o;
+    }
+    int run = incl - s;
+    if (lane == 0) seg[0] = 0;
+    for (int i = lo; i < hi; ++i) {
+      run += seg[i + 1];
+      seg[i + 1] = run;
+    }
+  }
+  __syncthreads();
+  if (b == 0) {
+    for (int e = tid; e < E; e += kDispThreads) {
+      kept[e] = tot[e];
+      buf_expert[rank[e]] = e;
+    }
+    for (int i = tid; i <= E; i += kDispThreads) seg_off[i] = seg[i];
+    // node nu starts where its first expert starts: the number of kept rows on lower nodes
+    for (int nu = tid; nu <= N; nu += kDispThreads) {
+      int s = 0;
+      for (int e = 0; e < E; ++e) s += node[e] < nu ? tot[e] : 0;
+      node_off[nu] = s;
+    }
+  }
+
+  // rank of each token among the block's earlier tokens of the same expert
+  const int wbase = b * kDispatchTokensPerBlock + wave * kTokPerWave;
+  int my_e[kIter], my_p[kIter];
+  int32_t* wc = wcnt + wave * E;
+#pragma unroll
+  for (int k = 0; k < kIter; ++k) {
+    const int m = wbase + k * kWave + lane;
+    const bool valid = m < T;
+    const int e = valid ? eid[m] : 0;
+    unsigned long long peers = __ballot(valid);
+    for (int bit = 0; bit < nbits; ++bit) {
+      const bool set = (e >> bit) & 1;
+      const unsigned long long bm = __ballot(valid && set);
+      peers &= set ? bm : ~bm;
+    }
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    const int before = __popcll(peers & lt);
+    int p = 0;
+    if (valid) p = wc[e] + before;       // all lanes read the wave's running count ...
+    wave_sync();
+    if (valid && before == 0) wc[e] = p + __popcll(peers);  // ... then each group's first lane advances it
+    wave_sync();
+    my_e[k] = valid ? e : -1;
+    my_p[k] = p;
+  }
+  __syncthreads();
+  // ordered prefix over the block's waves (in place: wcnt[w][e] := tokens of e in waves < w)
+  for (int e = tid; e < E; e += kDispThreads) {
+    int run = off[e];
+#pragma unroll
+    for (int q = 0; q < kDispWaves; ++q) {
+      const int c = wcnt[q * E + e];
+      wcnt[q * E + e] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kIter; ++k) {
+    const int m = wbase + k * kWave + lane;
+    const int e = my_e[k];
+    if (e >= 0) {
+      const int p = wc[e] + my_p[k];
+      pos[m] = p;
+      int s = -1;
+      if (p < C) {
+        s = seg[rank[e]] + p;
+        row_token[s] = m;
+      }
+      slot[m] = s;
+    }
+  }
+}
+
+// send[r,:] = x[row_token[r],:].  A row is `chunks` 16-byte vectors; LPR lanes share a row.
+template <int LPR>
+__global__ __launch_bounds__(kDispThreads) void dispatch_copy_kernel(const uint4* __restrict__ x,
+                                                                     const int32_t* __restrict__ row_token,
+                                                                     const int32_t* __restrict__ seg_off,
+                                                                     uint4* __restrict__ send, int E, int chunks) {
+  constexpr int RPB = kDispThreads / LPR;
+  const int K = seg_off[E];
+  const int r = blockIdx.x * RPB + threadIdx.x / LPR;
+  if (r >= K) return;
+  const int l = threadIdx.x % LPR;
+  const uint4* src = x + (size_t)row_token[r] * chunks;
+  uint4* dst = send + (size_t)r * chunks;
+  constexpr int U = 4;
+  int c = l;
+  for (; c + (U - 1) * LPR < chunks; c += U * LPR) {
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = nt_load16(src + c + u * LPR);
+#pragma unroll
+    for (int u = 0; u < U; ++u) nt_store16(v[u], dst + c + u * LPR);
+  }
+  for (; c < chunks; c += LPR) dst[c] = src[c];
+}
+
+template <int LPR>
+void launch_copy(const void* x, const int32_t* row_token, const int32_t* seg_off, void* send, int E, int rows,
+                 int chunks, hipStream_t st) {
+  constexpr int RPB = kDispThreads / LPR;
+  hipLaunchKernelGGL((dispatch_copy_kernel<LPR>), dim3(ceil_div(rows, RPB)), dim3(kDispThreads), 0, st,
+                     (const uint4*)x, row_token, seg_off, (uint4*)send, E, chunks);
+}
+
+}  // namespace
+}  // namespace locmoe
+
+extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n,
+                               int32_t* pos, int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off,
+                               int32_t* buf_expert, int32_t* row_token, void* send, void* ws, size_t ws_bytes,
+                               void* stream) {
+  using namespace locmoe;
+  if (!desc || !x || !eid || !pos || !slot || !kept || !seg_off || !node_off || !buf_expert || !row_token ||
+      !send)
+    return LOCMOE_ERR_NULL;
+  int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  if (!e2n && desc->E % desc->N != 0) return LOCMOE_ERR_SHAPE;
+  if (!ws || ws_bytes < locmoe_workspace_bytes(desc)) return LOCMOE_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  const int T = desc->T, E = desc->E;
+  const int nblocks = ceil_div(T, kDispatchTokensPerBlock);
+  int32_t* blockcnt = (int32_t*)ws;
+  hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblocks), dim3(kDispThreads), (size_t)E * 4, s, eid, blockcnt, T,
+                     E);
+  st = launch_status();
+  if (st != LOCMOE_OK) return st;
+  int nbits = 0;
+  while ((1 << nbits) < E) ++nbits;
+  const size_t smem = ((size_t)E * 5 + 1 + (size_t)kDispWaves * E) * 4;
+  hipLaunchKernelGGL(dispatch_slots_kernel, dim3(nblocks), dim3(kDispThreads), smem, s, eid, e2n, blockcnt, pos,
+                     slot, kept, seg_off, node_off, buf_expert, row_token, T, E, desc->N, desc->C, nblocks, nbits);
+  st = launch_status();
+  if (st != LOCMOE_OK) return st;
+  // at most min(T, E*C) rows can be kept; the kernel reads the real K from seg_off[E]
+  const long long cap = (long long)E * desc->C;
+  const int rows = (int)(cap < T ? cap : T);
+  const int chunks = desc->d * (desc->x_dtype == LOCMOE_BF16 ? 2 : 4) / 16;
+  if (chunks >= 256) launch_copy<256>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 128) launch_copy<128>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 64) launch_copy<64>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 32) launch_copy<32>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 16) launch_copy<16>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else launch_copy<8>(x, row_token, seg_off, send, E, rows, chunks, s);
+  return launch_status();
+}

@@ -1,0 +1,326 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars (also in the design doc):
+  * routing assignments, positions, slots, kept/segment/node offsets, row_token, dropped set and
+    the send buffer rows: bit-exact, given the oracle's float32 gating values;
+  * gating values: relative L2 <= 1e-5 and |diff| <= 1e-5 * (E/d) * sum_j |x_j| per element;
+  * scores w, Psum and the loss scalars: 1e-5 relative;
+  * FFN output and y: relative L2 <= 1e-2 against the float64 oracle (which rounds nothing; the
+    budget covers bf16 rounding of H, out and y).
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import locmoe_oracle as orc
+from paper_2401_13920_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2401_13920_amd import harness, locmoe as lm
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lm.lib()
+    return torch, lm, harness
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def i32(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def check_gate(env, c, x, x_dev, desc, g_dev):
+    torch, lm, hz = env
+    lm.locmoe_gate(desc, x_dev, g_dev)
+    torch.cuda.synchronize()
+    g = g_dev.cpu().numpy()
+    ref = orc.gate(x, c.E)
+    assert rel_l2(g, ref) <= 1e-5
+    blk = c.d // c.E
+    bound = 1e-5 * np.abs(x.astype(np.float64)).reshape(len(x), c.E, blk).sum(axis=2) / blk
+    assert np.all(np.abs(g - ref) <= bound + 1e-30)
+    return ref.astype(np.float32)
+
+
+def check_route(env, c, desc, b, g32, eps, home, e2n, relu, alpha, mu):
+    torch, lm, hz = env
+    g_dev = torch.from_numpy(g32).cuda()
+    eps_dev = None if eps is None else torch.from_numpy(eps.astype(np.float32)).cuda()
+    home_dev = None if home is None else i32(torch, home)
+    e2n_dev = None if e2n is None else i32(torch, e2n)
+    lm.locmoe_route(desc, g_dev, eps_dev, home_dev, e2n_dev, b.eid, b.w, b.cnt, b.Psum, b.stats, b.ws, b.ws_bytes)
+    torch.cuda.synchronize()
+    eid, w, p, _ = orc.route(g32, eps, relu)
+    e2n_full = e2n if e2n is not None else np.arange(c.E) // (c.E // c.N)
+    st = orc.route_stats(eid, p, home, e2n_full, c.N, alpha, mu)
+    assert np.array_equal(b.eid.cpu().numpy(), eid)                      # bit-exact assignments
+    assert np.allclose(b.w.cpu().numpy(), w, rtol=1e-5, atol=0)
+    assert np.array_equal(b.cnt.cpu().numpy(), st["cnt"])
+    assert np.allclose(b.Psum.cpu().numpy(), st["Psum"], rtol=1e-5, atol=1e-7)
+    s = b.stats.cpu().numpy()
+    for k, name in enumerate(["L_aux", "KL_hard", "KL_soft", "L_loc", "locality_frac"]):
+        assert s[k] == pytest.approx(st[name], rel=1e-5, abs=2e-7), name
+    assert s[5] == st["cnt"].max() and s[6] == int((st["cnt"] == 0).sum())
+    return eid, w
+
+
+def check_dispatch(env, c, desc, b, x, x_dev, eid, e2n, C):
+    torch, lm, hz = env
+    e2n_dev = None if e2n is None else i32(torch, e2n)
+    e2n_full = e2n if e2n is not None else np.arange(c.E) // (c.E // c.N)
+    b.send.zero_()
+    lm.locmoe_dispatch(desc, x_dev, i32(torch, eid), e2n_dev, b.pos, b.slot, b.kept, b.seg_off, b.node_off,
+                       b.buf_expert, b.row_token, b.send, b.ws, b.ws_bytes)
+    torch.cuda.synchronize()
+    s = orc.slots(eid, c.E, C, np.asarray(e2n_full), c.N)
+    K = int(s["seg_off"][-1])
+    for name in ("pos", "slot", "kept", "seg_off", "node_off", "buf_expert"):
+        assert np.array_equal(getattr(b, name).cpu().numpy(), s[name]), name
+    assert np.array_equal(b.row_token.cpu().numpy()[:K], s["row_token"])
+    send = hz.to_host_f32(b.send[:K])
+    assert np.array_equal(send, x[s["row_token"]])                          # bit copies of the rows
+    return s, K
+
+
+def check_ffn(env, c, desc, b, x, s, K, W_in_dev, W_out_dev, weights, sample=None):
+    """FFN on the oracle's send buffer; full compare, or only the listed buffer rows."""
+    torch, lm, hz = env
+    b.send[:K].copy_(hz.to_device(x[s["row_token"]], c.dtype))
+    b.seg_off.copy_(i32(torch, s["seg_off"])); b.buf_expert.copy_(i32(torch, s["buf_expert"]))
+    b.out.zero_()
+    lm.locmoe_expert_ffn(desc, b.send, b.seg_off, b.buf_expert, W_in_dev, W_out_dev, b.H, b.out)
+    torch.cuda.synchronize()
+    if sample is None:
+        ref = orc.expert_ffn(x[s["row_token"]], s["seg_off"], s["buf_expert"], weights)
+        got = hz.to_host_f32(b.out[:K])
+        assert rel_l2(got, ref) <= 1e-2
+        if K:
+            rows = np.linalg.norm(got - ref, axis=1) / (np.linalg.norm(ref, axis=1) + 1e-30)
+            assert rows.max() <= 3e-2                                        # no single row is off
+        return ref
+    for r in sample:
+        rank = int(np.searchsorted(s["seg_off"], r, side="right") - 1)
+        e = int(s["buf_expert"][rank])
+        W_in, W_out = weights(e)
+        ref = orc.ffn_rows(x[s["row_token"][r]][None, :], W_in, W_out)[0]
+        got = hz.to_host_f32(b.out[r])
+        assert rel_l2(got, ref) <= 1e-2, (r, e)
+    return None
+
+
+def check_combine(env, c, desc, b, out_ref, slot, w):
+    """Combine alone on a given out buffer: the only rounding is the final store."""
+    torch, lm, hz = env
+    K = out_ref.shape[0]
+    out_st = wl.round_to_storage(out_ref.astype(np.float32), c.dtype)
+    if K:
+        b.out[:K].copy_(hz.to_device(out_st, c.dtype))
+    w32 = w.astype(np.float32)
+    lm.locmoe_combine(desc, b.out, i32(torch, slot), torch.from_numpy(w32).cuda(), b.y)
+    torch.cuda.synchronize()
+    y = hz.to_host_f32(b.y)
+    ref = orc.combine(out_st.astype(np.float64), slot, w32.astype(np.float64))
+    assert np.all(y[slot < 0] == 0)
+    tol = 2.0 ** -8 if c.dtype == "bf16" else 2.0 ** -23
+    assert np.all(np.abs(y - ref) <= tol * np.abs(ref) + 1e-37)
+
+
+def run_full(env, c, C, *, T=None, eps=None, relu=True, e2n=None, use_home=True, alpha=wl.ALPHA, mu=wl.MU):
+    """Every step against the oracle, element by element, then the chained path end to end."""
+    torch, lm, hz = env
+    say(f"[case] cfg={c.cfg} T={T or c.T} d={c.d} E={c.E} N={c.N} h={c.h} C={C} dtype={c.dtype} relu={relu} "
+        f"eps={'y' if eps is not None else 'n'} e2n={'custom' if e2n is not None else 'default'}")
+    x, home = wl.hidden_states(c, T)
+    T = len(x)
+    if not use_home:
+        home = None
+    desc = lm.make_desc(T, c.d, c.E, c.N, c.h, C, c.dtype, relu, alpha, mu)
+    b = lm.alloc_buffers(desc)
+    x_dev = hz.to_device(x, c.dtype)
+    g32 = check_gate(env, c, x, x_dev, desc, b.g)
+    eid, w = check_route(env, c, desc, b, g32, eps, home, e2n, relu, alpha, mu)
+    s, K = check_dispatch(env, c, desc, b, x, x_dev, eid, e2n, C)
+    ws = {e: wl.expert_weights(c, e) for e in range(c.E)}
+    W_in = torch.stack([hz.to_device(ws[e][0], "bf16") for e in range(c.E)])
+    W_out = torch.stack([hz.to_device(ws[e][1], "bf16") for e in range(c.E)])
+    out_ref = check_ffn(env, c, desc, b, x, s, K, W_in, W_out, lambda e: ws[e])
+    check_combine(env, c, desc, b, out_ref, s["slot"], w)
+    # end to end on the GPU's own intermediates
+    b2 = lm.alloc_buffers(desc)
+    eps_dev = None if eps is None else torch.from_numpy(eps.astype(np.float32)).cuda()
+    lm.forward(desc, x_dev, None if home is None else i32(torch, home), None if e2n is None else i32(torch, e2n),
+               W_in, W_out, b2, eps=eps_dev)
+    torch.cuda.synchronize()
+    eid_gpu = b2.eid.cpu().numpy()
+    nflip = int((eid_gpu != eid).sum())
+    say(f"        K={K} dropped={T - K} eid flips vs oracle (near ties only)={nflip}")
+    if nflip == 0:
+        y_ref = orc.combine(out_ref, s["slot"], w)
+        assert np.array_equal(b2.slot.cpu().numpy(), s["slot"])
+        assert rel_l2(hz.to_host_f32(b2.y), y_ref) <= 1e-2
+    else:
+        # a flip is legitimate only where the two best float64 scores agree to fp32 rounding
+        g64 = orc.gate(x, c.E)
+        for m in np.nonzero(eid_gpu != eid)[0]:
+            assert abs(g64[m, eid_gpu[m]] - g64[m, eid[m]]) <= 1e-5 * np.abs(x[m]).mean()
+    return b2
+
+
+# ------------------------------------------------------------------------------------------
+def test_config1_fp32(env):
+    c = wl.CONFIGS[1]
+    run_full(env, c, c.C)
+    run_full(env, c, 1)                       # the paper's measured delta: bound < 1 token
+
+
+def test_config2_bf16(env):
+    c = wl.CONFIGS[2]
+    run_full(env, c, c.C)
+
+
+def test_small_odd_shapes(env):
+    c = wl.small_config()                     # T=96 d=48 E=6 N=3 h=40: nothing is a tile multiple
+    run_full(env, c, 9)
+    run_full(env, c, 200)                     # capacity above every count: nothing dropped
+    run_full(env, wl.small_config(dtype="f32"), 5)
+    e2n = np.array([2, 0, 1, 1, 0, 2], np.int32)
+    eps = np.array([0.3, -0.2, 0.0, 0.5, -1.0, 0.1], np.float32)
+    run_full(env, c, 9, eps=eps, e2n=e2n)
+    run_full(env, c, 9, relu=False, use_home=False)
+    run_full(env, wl.small_config(T=1, E=3, N=1, d=24, h=8), 1)
+    run_full(env, wl.small_config(T=5, E=1, N=1, d=8, h=8), 2)
+
+
+def test_ragged_token_counts_and_wide_experts(env):
+    # T not a multiple of any block size; E=128 with 40-wide blocks (5 chunks: the LDS gate path)
+    run_full(env, wl.small_config(T=2500, d=5120, E=128, N=16, h=64, clusters=9), 7)
+    # E=200 > 64 lanes: several experts per lane in the router; 8-wide blocks
+    run_full(env, wl.small_config(T=1111, d=1600, E=200, N=8, h=16, clusters=9), 3)
+    # 12-wide blocks: not a whole number of 16-byte chunks -> scalar gate path
+    run_full(env, wl.small_config(T=300, d=96, E=8, N=2, h=24), 20)
+    run_full(env, wl.small_config(T=300, d=96, E=8, N=2, h=24, dtype="f32"), 20)
+
+
+def test_tuned_gemm_tiles_with_ragged_segments(env):
+    # d, h multiples of the tuned tile; capacity spans several 256-row tiles with ragged tails
+    run_full(env, wl.small_config(T=4096, d=256, E=4, N=2, h=512, clusters=3), 700)
+    run_full(env, wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4, dtype="bf16"), 300)
+
+
+def test_route_dispatch_deterministic(env):
+    torch, lm, hz = env
+    c = wl.CONFIGS[2]
+    x, home = wl.hidden_states(c)
+    desc = lm.make_desc(c.T, c.d, c.E, c.N, c.h, c.C, c.dtype)
+    b = lm.alloc_buffers(desc)
+    x_dev = hz.to_device(x, c.dtype); home_dev = i32(torch, home)
+    first = None
+    for it in range(10):
+        lm.locmoe_gate(desc, x_dev, b.g)
+        lm.locmoe_route(desc, b.g, None, home_dev, None, b.eid, b.w, b.cnt, b.Psum, b.stats, b.ws, b.ws_bytes)
+        lm.locmoe_dispatch(desc, x_dev, b.eid, None, b.pos, b.slot, b.kept, b.seg_off, b.node_off, b.buf_expert,
+                           b.row_token, b.send, b.ws, b.ws_bytes)
+        torch.cuda.synchronize()
+        K = int(b.seg_off[-1])
+        cur = [t.cpu().numpy().tobytes() for t in (b.eid, b.w, b.Psum, b.stats, b.pos, b.slot, b.row_token[:K])]
+        first = first or cur
+        assert cur == first
+
+
+# ------------------------------------------------------------------------------------------
+# Full-size workloads: routing and dispatch element by element, FFN / y on sampled rows.
+# ------------------------------------------------------------------------------------------
+def run_big(env, c, C, with_ffn=True):
+    torch, lm, hz = env
+    say(f"[big] cfg={c.cfg} T={c.T} d={c.d} E={c.E} h={c.h} C={C}")
+    t0 = time.time()
+    x, home = wl.hidden_states(c)
+    say(f"      inputs {time.time() - t0:.1f}s")
+    desc = lm.make_desc(c.T, c.d, c.E, c.N, c.h, C, c.dtype)
+    b = lm.alloc_buffers(desc)
+    x_dev = hz.to_device(x, c.dtype)
+    g32 = check_gate(env, c, x, x_dev, desc, b.g)
+    eid, w = check_route(env, c, desc, b, g32, None, home, None, True, wl.ALPHA, wl.MU)
+    s, K = check_dispatch(env, c, desc, b, x, x_dev, eid, None, C)
+    say(f"      gate/route/dispatch ok, K={K} dropped={c.T - K} ({time.time() - t0:.1f}s)")
+    if not with_ffn:
+        rng = np.random.default_rng(1)
+        out_ref = rng.standard_normal((K, c.d)).astype(np.float32)
+        check_combine(env, c, desc, b, out_ref, s["slot"], w)
+        return
+    # experts to sample: first and last in the buffer, the fullest, the emptiest non-empty one
+    kept = s["kept"]
+    cand = {int(s["buf_expert"][0]), int(s["buf_expert"][-1]), int(np.argmax(kept))}
+    nz = np.nonzero(kept)[0]
+    cand.add(int(nz[np.argmin(kept[nz])]))
+    W_in, W_out, host_w = hz.upload_weights(c, keep=cand, progress=lambda a, n: say(f"      weights {a}/{n}"))
+    say(f"      weights uploaded ({time.time() - t0:.1f}s)")
+    rank_of = {int(e): r for r, e in enumerate(s["buf_expert"])}
+    sample = []
+    for e in sorted(cand):
+        a, z = int(s["seg_off"][rank_of[e]]), int(s["seg_off"][rank_of[e] + 1])
+        if z > a:
+            sample += sorted({a, (a + z) // 2, z - 1, min(z - 1, a + 255), min(z - 1, a + 256)})
+    check_ffn(env, c, desc, b, x, s, K, W_in, W_out, lambda e: host_w[e], sample=sample)
+    say(f"      ffn sampled rows ok: {len(sample)} rows of experts {sorted(cand)} ({time.time() - t0:.1f}s)")
+    # the chained path in the benchmark's launch configuration, y on the sampled tokens
+    b2 = lm.alloc_buffers(desc)
+    lm.forward(desc, x_dev, i32(torch, home), None, W_in, W_out, b2)
+    torch.cuda.synchronize()
+    eid_gpu = b2.eid.cpu().numpy()
+    flips = np.nonzero(eid_gpu != eid)[0]
+    say(f"      end-to-end eid flips vs oracle: {len(flips)}")
+    g64 = orc.gate(x, c.E) if len(flips) else None
+    for m in flips:
+        assert abs(g64[m, eid_gpu[m]] - g64[m, eid[m]]) <= 1e-5 * np.abs(x[m]).mean()
+    if len(flips) == 0:
+        y = b2.y
+        for r in sample:
+            m = int(s["row_token"][r])
+            e = int(eid[m])
+            ref = w[m] * orc.ffn_rows(x[m][None, :], *host_w[e])[0]
+            assert rel_l2(hz.to_host_f32(y[m]), ref) <= 1e-2
+        dropped = np.nonzero(s["slot"] < 0)[0][:64]
+        assert float(y[torch.from_numpy(dropped).cuda()].abs().max()) == 0.0 if len(dropped) else True
+    # properties that hold at any size
+    y_host_norm = b2.y.float().norm(dim=1).cpu().numpy()
+    assert np.all((y_host_norm > 0) == (b2.slot.cpu().numpy() >= 0))
+
+
+def test_config3_full_size_capacity_sweep(env):
+    c = wl.CONFIGS[3]
+    torch, lm, hz = env
+    x, home = wl.hidden_states(c)
+    x_dev = hz.to_device(x, c.dtype)
+    g32 = orc.gate(x, c.E).astype(np.float32)
+    eid, w, _, _ = orc.route(g32)
+    for C in (c.C, 1024, 1280, 2048, 1):
+        say(f"[big] cfg=3 dispatch sweep C={C}")
+        desc = lm.make_desc(c.T, c.d, c.E, c.N, c.h, C, c.dtype)
+        b = lm.alloc_buffers(desc)
+        check_dispatch(env, c, desc, b, x, x_dev, eid, None, C)
+
+
+def test_config4_full_size_headline(env):
+    c = wl.CONFIGS[4]
+    run_big(env, c, c.C)
+
+
+def test_config5_full_size_routing_stress(env):
+    c = wl.CONFIGS[5]
+    run_big(env, c, c.C, with_ffn=False)
