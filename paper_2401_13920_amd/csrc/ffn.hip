@@ -160,23 +160,26 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) acc[ni][mi] = (f32x16){0};
 
-  uint4 ra[4], rb[4];
+  // The staging registers are native vectors and the loop body has no conditionals: the prefetch
+  // of the tile after the last one is clamped to the last tile (redundant, never consumed).  With
+  // branches around the prefetch the compiler demotes these arrays to scratch memory and
+  // serialises every load.
+  u32x4 ra[4], rb[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { ra[i] = *(const uint4*)(ga[i]); rb[i] = *(const uint4*)(gb[i]); }
+  for (int i = 0; i < 4; ++i) { ra[i] = *(const u32x4*)(ga[i]); rb[i] = *(const u32x4*)(gb[i]); }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    *(uint4*)(smem + lds_w[i]) = ra[i];
-    *(uint4*)(smem + kBM * kBK * 2 + lds_w[i]) = rb[i];
+    *(u32x4*)(smem + lds_w[i]) = ra[i];
+    *(u32x4*)(smem + kBM * kBK * 2 + lds_w[i]) = rb[i];
   }
   __syncthreads();
 
   const int KT = Kdim / kBK;
   for (int kt = 0; kt < KT; ++kt) {
-    const bool more = kt + 1 < KT;
-    if (more) {
-      const int ko = (kt + 1) * kBK;
+    {
+      const int ko = min(kt + 1, KT - 1) * kBK;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { ra[i] = *(const uint4*)(ga[i] + ko); rb[i] = *(const uint4*)(gb[i] + ko); }
+      for (int i = 0; i < 4; ++i) { ra[i] = *(const u32x4*)(ga[i] + ko); rb[i] = *(const u32x4*)(gb[i] + ko); }
     }
     const char* sa = smem + (kt & 1) * kStageBytes;
     const char* sb = sa + kBM * kBK * 2;
@@ -193,12 +196,12 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi) acc[ni][mi] = mfma_bf16(fb[ni], fa[mi], acc[ni][mi]);
     }
-    if (more) {
+    {
       char* da = smem + ((kt + 1) & 1) * kStageBytes;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        *(uint4*)(da + lds_w[i]) = ra[i];
-        *(uint4*)(da + kBM * kBK * 2 + lds_w[i]) = rb[i];
+        *(u32x4*)(da + lds_w[i]) = ra[i];
+        *(u32x4*)(da + kBM * kBK * 2 + lds_w[i]) = rb[i];
       }
     }
     __syncthreads();
