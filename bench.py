@@ -100,6 +100,14 @@ def main() -> int:
     log(f"[bench] config {c.cfg}: T={c.T} d={c.d} E={c.E} N={c.N} h={c.h} C={C}; inputs {time.time() - t0:.1f}s")
     W_in, W_out, _ = hz.upload_weights(c, progress=lambda a, n: log(f"[bench] weights {a}/{n}"))
     log(f"[bench] weights resident {time.time() - t0:.1f}s")
+    W_in_rm, W_out_rm = W_in, W_out          # row-major copies stay for the CPU baseline
+    if lm.locmoe_packed_weights_bytes(desc) and c.dtype == "bf16":
+        # one-time re-tiling of the static weights (outside the timed region)
+        W_in = torch.empty_like(W_in_rm); W_out = torch.empty_like(W_out_rm)
+        lm.locmoe_pack_weights(desc, W_in_rm, W_out_rm, W_in, W_out)
+        torch.cuda.synchronize()
+        desc.w_packed = 1
+        log(f"[bench] weights packed {time.time() - t0:.1f}s")
     i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
     x0 = hz.to_device(x, c.dtype)
     # rotating sets: the same tokens rolled by a different offset (distinct memory, same statistics)
@@ -164,7 +172,8 @@ def main() -> int:
                            "mfma_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
     dom = "ffn_in" if ms["ffn_in"] >= ms["ffn_out"] else "ffn_out"
     achieved = flops / (ms[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"ffn_gemm_256 ({dom})", "achieved": round(achieved, 2),
+    kname = "ffn_gemm_dma" if desc.w_packed else "ffn_gemm_256"
+    roofline = {"bound": "mfma", "kernel": f"{kname} ({dom})", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": None, "flops_per_launch": flops, "ms_per_launch": round(ms[dom], 4)}
 
@@ -183,7 +192,7 @@ def main() -> int:
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle (bounded sample)...")
-        result["cpu_baseline"] = cpu_baseline(c, C, x, home, W_in, W_out)
+        result["cpu_baseline"] = cpu_baseline(c, C, x, home, W_in_rm, W_out_rm)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)

@@ -48,6 +48,7 @@ typedef struct locmoe_desc {
   int32_t T, d, E, N, h, C;
   int32_t x_dtype; /* LOCMOE_F32 or LOCMOE_BF16 */
   int32_t relu;    /* 1: G = ReLU(g + eps) as printed below Eq. 3; 0: G = g + eps */
+  int32_t w_packed; /* 0: W_in/W_out row-major; 1: both in the layout written by locmoe_pack_weights */
   float alpha;     /* auxiliary-loss weight of Eq. 5 (the paper uses 0.01) */
   float mu;        /* locality-loss weight of Eq. 6 (left open by the paper) */
 } locmoe_desc;
@@ -128,6 +129,19 @@ int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int32_t* eid, 
 int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
                       const int32_t* buf_expert, const void* W_in, const void* W_out, void* H_ws,
                       void* out, void* stream);
+
+/* One-time re-tiling of the static expert weights for the direct-to-LDS grouped GEMM (not part of
+ * the timed path).  Needs d % 256 == 0, h % 256 == 0 and bf16 activations (x_dtype = LOCMOE_BF16);
+ * locmoe_packed_weights_bytes returns the size of EACH packed tensor (E*h*d*2 bytes), or 0 when the
+ * shape cannot be packed.  Packed layout: for expert e, 256-row tile nt and 32-column step kt, a
+ * 16 KiB block at ((e*NT + nt)*KT + kt)*16 KiB whose 16-byte chunk p holds row r = p/4 of the tile,
+ * columns 8*c .. 8*c+7 of the step with c = (p%4) ^ ((r/4)%4) - the LDS image the kernel consumes.
+ * With desc->w_packed = 1 the three expert_ffn entry points take the packed tensors in place of
+ * W_in / W_out (LOCMOE_ERR_ARG if the shape or dtype cannot use them); results are the same
+ * to rounding order.  W_in [E,h,d], W_out [E,d,h] device bf16 (read); packed tensors device (written). */
+size_t locmoe_packed_weights_bytes(const locmoe_desc* desc);
+int locmoe_pack_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_packed,
+                        void* W_out_packed, void* stream);
 
 /* The two linear transformations of Eq. 1 as separate launches (locmoe_expert_ffn is exactly
  * _in followed by _out on the same stream); same buffers, layouts and errors as above.

@@ -5,18 +5,37 @@
 // contract over the contiguous axis of both operands ("NT" form): every MFMA fragment is one
 // 16-byte LDS read.  bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
+// Three kernels share the operand orientation and the epilogue:
+//   ffn_gemm_generic  any shape the descriptor allows, fp32 or bf16 activations (fallback)
+//   ffn_gemm_256      256x256x64 tiles, register-staged double buffer, row-major weights
+//   ffn_gemm_dma      256x256x32 tiles, five LDS stages filled by direct-to-LDS loads, weights
+//                     pre-packed by locmoe_pack_weights into the LDS image of each stage
+//
 // The weight rows feed the MFMA's A operand and the activation rows its B operand, i.e. the
 // tile is computed transposed (D[n][m]); a lane then owns 4 consecutive output columns n of one
 // row m per accumulator quad and stores them as one 8-byte (bf16) or 16-byte (fp32) vector.
 #include <math.h>
+
+#include <type_traits>
 
 #include "common.h"
 
 namespace locmoe {
 namespace {
 
-__device__ __forceinline__ float gelu_erf(float v) {  // v * Phi(v)
-  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+// GeLU(v) = v * Phi(v) with Phi(v) = 1 - erfc(v/sqrt2)/2.  erfc(x), x >= 0, is evaluated with the rational
+// form of Abramowitz & Stegun 7.1.26, erfc(x) = (a1 t + ... + a5 t^5) exp(-x^2), t = 1/(1 + p x), whose
+// absolute error is below 1.5e-7; the negative side uses Phi(v) = erfc(|v|/sqrt2)/2 directly, so the
+// tail does not cancel.  Straight-line code: one reciprocal, one exp2, no branches.
+__device__ __forceinline__ float gelu_erf(float v) {
+  const float x = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float half_erfc = 0.5f * p * t * __builtin_amdgcn_exp2f(-1.44269504088896341f * x * x);
+  return v * (v < 0.f ? half_erfc : 1.0f - half_erfc);
 }
 
 __device__ __forceinline__ f32x16 mfma_bf16(const bf16x8& a, const bf16x8& b, const f32x16& c) {
@@ -103,8 +122,8 @@ __global__ __launch_bounds__(kGenThreads) void ffn_gemm_generic(const void* __re
 
 // ---------------------------------------------------------------------------------------------
 // Tuned kernel: 256x256x64 tile, 8 waves (2 along m x 4 along n, 128x64 per wave), double
-// buffered LDS (2 x 64 KiB), XOR-swizzled 16-byte slots, bf16 activations, K % 64 == 0,
-// N % 256 == 0.  Work-group ids are remapped so that each XCD (ids congruent mod 8 land on one
+// buffered LDS (2 x 64 KiB), XOR-swizzled 16-byte slots (slot = chunk ^ (row/2 mod 8): 16 lanes
+// reading 16 consecutive rows touch all 64 banks once), bf16 activations, K % 64 == 0, N % 256 == 0.  Work-group ids are remapped so that each XCD (ids congruent mod 8 land on one
 // XCD and share its L2) walks a contiguous range of experts, with the m-tiles that share a
 // weight tile adjacent in time.
 // ---------------------------------------------------------------------------------------------
@@ -223,6 +242,226 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// DMA kernel: 256x256 tile, BK = 32, 8 waves (2 along m x 4 along n, 128x64 per wave), kStages LDS
+// stages of 32 KiB filled by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers,
+// no ds_write), so up to two stages (64 KiB per CU) are in flight while two are being consumed.
+//
+// LDS image of a stage: A rows then B rows, 64 bytes (4 chunks of 8 bf16) per row, chunk kc of row r
+// in slot kc ^ (r/4 mod 4): 16 lanes reading 16 consecutive rows touch all 64 banks once.  A
+// direct-to-LDS load writes lane l's 16 bytes at base + 16 l, so the image is produced by choosing
+// which global chunk each lane fetches; packed weights are stored as that image already, which
+// makes the weight stream of a work-group one contiguous run of 16 KiB blocks.
+//
+// The compiler does not know about these loads (inline asm), so the vmcnt accounting is explicit:
+// every wave issues kLoadsPerStage loads per stage, loads complete in order, and nothing else in
+// the K loop uses vmcnt.  Pipeline invariant at the top of iteration kt: stages kt and kt+1 are
+// complete and visible; F[0] holds the fragments of (kt, k-step 0).
+//
+// Rows of the tile are owned in interleaved 32-row subtiles (wave row wm owns subtiles wm, wm+2,
+// ...), so a ragged tile skips MFMAs evenly across waves.
+// ---------------------------------------------------------------------------------------------
+constexpr int kDmaBK = 32;
+constexpr int kDmaThreads = 512;
+constexpr int kDmaStage = (kBM + kBN) * kDmaBK * 2;  // 32 KiB
+constexpr int kStages = 5;
+constexpr int kDmaSmem = kStages * kDmaStage;         // 160 KiB: the whole LDS of a CU
+constexpr int kLoadsPerStage = 4;                      // per wave: 2 A blocks + 2 B blocks of 1 KiB
+constexpr int kPackBlock = kBN * kDmaBK * 2;           // 16 KiB: one packed weight block
+
+typedef const char __attribute__((address_space(3))) * lds_cptr;
+
+// One wave-wide 1 KiB copy global -> LDS: lane l reads 16 bytes at sbase + voff and they land at
+// LDS byte address lds_base + 16 l (M0 carries the wave-uniform LDS base).
+__device__ __forceinline__ void dma_1k(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase),
+               "s"(lds_base)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int NMI, bool GELU>
+__device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const char* __restrict__ Wbase,
+                                         uint16_t* __restrict__ Cout, uint32_t lds0, uint32_t offA0, uint32_t offA1,
+                                         uint32_t offB0, uint32_t offB1, int KT, int wm, int wn, int lane, int wave,
+                                         int rows_left, size_t crow0, int ldc, int n_base) {
+  const int khalf = lane >> 5;
+  lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
+  int a_addr[4], b_addr[2], a_sw[4], b_sw[2];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    const int r = (2 * mi + wm) * 32 + (lane & 31);
+    a_addr[mi] = r * 64;
+    a_sw[mi] = (r >> 2) & 3;
+  }
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni) {
+    const int r = wn * 64 + ni * 32 + (lane & 31);
+    b_addr[ni] = kBM * 64 + r * 64;
+    b_sw[ni] = (r >> 2) & 3;
+  }
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) acc[ni][mi] = (f32x16){0};
+
+  // Tile t (clamped to the last one: the tail prefetches are redundant and never consumed) into
+  // stage t % kStages.  This wave copies A blocks {wave, wave+8} and B blocks {wave, wave+8}.
+  auto issue = [&](int t) {
+    const int kk = min(t, KT - 1);
+    const uint32_t st = lds0 + (uint32_t)(t % kStages) * kDmaStage;
+    const char* ab = Abase + (size_t)kk * (kDmaBK * 2);
+    const char* wb = Wbase + (size_t)kk * kPackBlock;
+    dma_1k(ab, offA0, st + wave * 1024);
+    dma_1k(ab, offA1, st + (wave + 8) * 1024);
+    dma_1k(wb, offB0, st + kBM * 64 + wave * 1024);
+    dma_1k(wb, offB1, st + kBM * 64 + (wave + 8) * 1024);
+  };
+  bf16x8 fa[2][4], fb[2][2];
+  auto fload = [&](auto buf, int t, int ks) {
+    constexpr int B = decltype(buf)::value;
+    const uint32_t so = (uint32_t)(t % kStages) * kDmaStage;
+    const int kc = ks * 2 + khalf;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+      fb[B][ni] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + so + b_addr[ni] + ((kc ^ b_sw[ni]) << 4));
+#pragma unroll
+    for (int mi = 0; mi < NMI; ++mi)
+      fa[B][mi] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + so + a_addr[mi] + ((kc ^ a_sw[mi]) << 4));
+  };
+  auto mma = [&](auto buf) {
+    constexpr int B = decltype(buf)::value;
+#pragma unroll
+    for (int mi = 0; mi < NMI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) acc[ni][mi] = mfma_bf16(fb[B][ni], fa[B][mi], acc[ni][mi]);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+
+#pragma unroll
+  for (int t = 0; t < kStages - 1; ++t) issue(t);
+  wait_vmcnt<kLoadsPerStage * (kStages - 3)>();  // tiles 0 and 1 have landed (this wave's share)
+  __syncthreads();                               // ... and everybody's
+  fload(I0{}, 0, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    fload(I1{}, kt, 1);
+    mma(I0{});
+    wait_vmcnt<kLoadsPerStage * (kStages - 4)>();  // tile kt+2 has landed (this wave's share)
+    __syncthreads();             // stage kt+2 complete for everybody; nobody reads stage kt-1 any more
+    issue(kt + kStages - 1);     // refill stage (kt-1) % kStages
+    fload(I0{}, kt + 1, 0);      // complete since the previous barrier (for kt+1 == KT: a clamped copy, unused)
+    mma(I1{});
+  }
+  wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
+
+#pragma unroll
+  for (int mi = 0; mi < NMI; ++mi) {
+    const int m = (2 * mi + wm) * 32 + (lane & 31);
+    if (m < rows_left) {
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int n = n_base + wn * 64 + ni * 32 + vq * 8 + khalf * 4;
+          store_quad<GELU, false>(Cout, crow0 + m, ldc, n, acc[ni][mi][vq * 4 + 0], acc[ni][mi][vq * 4 + 1],
+                                  acc[ni][mi][vq * 4 + 2], acc[ni][mi][vq * 4 + 3]);
+        }
+    }
+  }
+}
+
+template <bool GELU>
+__global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __restrict__ A,
+                                                            const uint16_t* __restrict__ Wp,
+                                                            uint16_t* __restrict__ Cout,
+                                                            const int32_t* __restrict__ seg_off,
+                                                            const int32_t* __restrict__ buf_expert, int Kdim,
+                                                            int Ndim, int MT, int NT, int total) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int id = blockIdx.x;
+  const int lin = (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
+  const int mt = lin % MT, nt = (lin / MT) % NT, r = lin / (MT * NT);
+  const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
+  const int m0 = mt * kBM;
+  if (m0 >= rows) return;
+  const int e = buf_expert[r];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int rows_left = rows - m0;
+  const char* Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
+  const char* Wbase = (const char*)(Wp + ((size_t)e * Ndim + (size_t)nt * kBN) * (size_t)Kdim);
+  // lane l of the copy of row block b: row 16 b + l/4, LDS slot l%4 receives chunk (l%4) ^ (row/4 mod 4).
+  // Rows past the segment's end re-read its last row (results masked at the store).
+  uint32_t offA[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = 16 * (wave + 8 * j) + (lane >> 2);
+    const int kc = (lane & 3) ^ ((row >> 2) & 3);
+    offA[j] = (uint32_t)min(row, rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
+  }
+  const uint32_t offB0 = (uint32_t)(wave * 1024 + lane * 16), offB1 = offB0 + 8 * 1024;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int KT = Kdim / kDmaBK;
+  const int nsub = min(8, (rows_left + 31) >> 5);  // live 32-row subtiles of this tile
+  const int nmi = (nsub - wm + 1) >> 1;            // ... of which this wave row owns nmi
+  const size_t crow0 = (size_t)seg0 + m0;
+  const int n_base = nt * kBN;
+#define LOCMOE_DMA_BODY(N)                                                                                    \
+  dma_body<N, GELU>(Abase, Wbase, Cout, lds0, offA[0], offA[1], offB0, offB1, KT, wm, wn, lane, wave, rows_left, \
+                    crow0, Ndim, n_base)
+  // every variant executes the same loads and barriers; a wave row without live subtiles runs the
+  // one-subtile variant on clamped rows and stores nothing
+  if (nmi >= 4) LOCMOE_DMA_BODY(4);
+  else if (nmi == 3) LOCMOE_DMA_BODY(3);
+  else if (nmi == 2) LOCMOE_DMA_BODY(2);
+  else LOCMOE_DMA_BODY(1);
+#undef LOCMOE_DMA_BODY
+}
+
+// Weight packing (one-time): block (e, nt, kt) of 16 KiB is the LDS image of W[e][nt*256 .. +256][kt*32 .. +32]:
+// 16-byte chunk p of the block holds row p/4, k-chunk (p%4) ^ (row/4 mod 4).
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint4* __restrict__ W, uint4* __restrict__ Wp,
+                                                           int Ndim, int Kdim, long long chunks) {
+  const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (q >= chunks) return;
+  const int KT = Kdim / kDmaBK, NT = Ndim / kBN;
+  const int p = (int)(q & 1023);
+  long long blk = q >> 10;
+  const int kt = (int)(blk % KT); blk /= KT;
+  const int nt = (int)(blk % NT);
+  const long long e = blk / NT;
+  const int row = p >> 2, kc = (p & 3) ^ ((row >> 2) & 3);
+  const long long src = ((e * Ndim + (long long)nt * kBN + row) * Kdim + (long long)kt * kDmaBK + kc * 8) / 8;
+  Wp[q] = W[src];
+}
+
+template <bool GELU>
+int launch_dma(const void* A, const void* Wp, void* C, const int32_t* seg_off, const int32_t* buf_expert, int E,
+               int rows_max, int Kdim, int Ndim, hipStream_t st) {
+  const int MT = ceil_div(rows_max, kBM), NT = Ndim / kBN;
+  const long long total = (long long)E * MT * NT;
+  if (total > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
+  auto kern = ffn_gemm_dma<GELU>;
+  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
+    return LOCMOE_ERR_HIP;
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
+                     (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT, (int)total);
+  return launch_status();
+}
+
+// shapes the packed layout and the DMA kernel support
+inline bool packable(const locmoe_desc* p) {
+  return p->d % kBN == 0 && p->h % kBN == 0 && (long long)p->d * 2 * 256 < 0x7FFFFFFFLL &&
+         (long long)p->h * 2 * 256 < 0x7FFFFFFFLL;
+}
+
 template <bool A_F32, bool GELU, bool OUT_F32>
 int launch_gemm(const void* A, const void* W, void* C, const int32_t* seg_off, const int32_t* buf_expert, int E,
                 int rows_max, int Kdim, int Ndim, hipStream_t st) {
@@ -230,7 +469,7 @@ int launch_gemm(const void* A, const void* W, void* C, const int32_t* seg_off, c
     const int MT = ceil_div(rows_max, kBM), NT = Ndim / kBN;
     const long long total = (long long)E * MT * NT;
     if (total <= 0x7FFFFFFFLL) {
-      auto kern = ffn_gemm_256<GELU, OUT_F32, 0>;
+      auto kern = ffn_gemm_256<GELU, OUT_F32, 1>;
       if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kFastSmem) !=
           hipSuccess)
         return LOCMOE_ERR_HIP;
@@ -256,6 +495,11 @@ extern "C" int locmoe_expert_ffn_in(const locmoe_desc* desc, const void* send, c
   const int st = check_desc(desc);
   if (st != LOCMOE_OK) return st;
   const int rows_max = desc->C < desc->T ? desc->C : desc->T;  // kept[e] <= min(C, T)
+  if (desc->w_packed) {
+    if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
+    return launch_dma<true>(send, W_in, H_ws, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h,
+                            as_stream(stream));
+  }
   if (desc->x_dtype == LOCMOE_F32)
     return launch_gemm<true, true, false>(send, W_in, H_ws, seg_off, buf_expert, desc->E, rows_max, desc->d,
                                           desc->h, as_stream(stream));
@@ -270,6 +514,11 @@ extern "C" int locmoe_expert_ffn_out(const locmoe_desc* desc, const void* H_ws, 
   const int st = check_desc(desc);
   if (st != LOCMOE_OK) return st;
   const int rows_max = desc->C < desc->T ? desc->C : desc->T;
+  if (desc->w_packed) {
+    if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
+    return launch_dma<false>(H_ws, W_out, out, seg_off, buf_expert, desc->E, rows_max, desc->h, desc->d,
+                             as_stream(stream));
+  }
   if (desc->x_dtype == LOCMOE_F32)
     return launch_gemm<false, false, true>(H_ws, W_out, out, seg_off, buf_expert, desc->E, rows_max, desc->h,
                                            desc->d, as_stream(stream));
@@ -284,4 +533,27 @@ extern "C" int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, cons
   const int st = locmoe_expert_ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, stream);
   if (st != LOCMOE_OK) return st;
   return locmoe_expert_ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, stream);
+}
+
+extern "C" size_t locmoe_packed_weights_bytes(const locmoe_desc* desc) {
+  using namespace locmoe;
+  if (check_desc(desc) != LOCMOE_OK || !packable(desc)) return 0;
+  return (size_t)desc->E * (size_t)desc->h * (size_t)desc->d * 2;
+}
+
+extern "C" int locmoe_pack_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_packed,
+                                   void* W_out_packed, void* stream) {
+  using namespace locmoe;
+  if (!desc || !W_in || !W_out || !W_in_packed || !W_out_packed) return LOCMOE_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  if (!packable(desc)) return LOCMOE_ERR_SHAPE;
+  const long long chunks = (long long)desc->E * desc->h * desc->d / 8;
+  const unsigned blocks = (unsigned)((chunks + 255) / 256);
+  hipStream_t s = as_stream(stream);
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(blocks), dim3(256), 0, s, (const uint4*)W_in, (uint4*)W_in_packed,
+                     desc->h, desc->d, chunks);  // W_in[e] is [h rows, d]: N = h, K = d
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(blocks), dim3(256), 0, s, (const uint4*)W_out, (uint4*)W_out_packed,
+                     desc->d, desc->h, chunks);  // W_out[e] is [d rows, h]: N = d, K = h
+  return launch_status();
 }

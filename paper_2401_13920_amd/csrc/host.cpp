@@ -16,6 +16,7 @@ int check_desc(const locmoe_desc* p) {
   if (p->C < 1) return LOCMOE_ERR_ARG;
   if (p->x_dtype != LOCMOE_F32 && p->x_dtype != LOCMOE_BF16) return LOCMOE_ERR_ARG;
   if (p->relu != 0 && p->relu != 1) return LOCMOE_ERR_ARG;
+  if (p->w_packed != 0 && p->w_packed != 1) return LOCMOE_ERR_ARG;
   if ((int64_t)p->E * (int64_t)p->C > (int64_t)std::numeric_limits<int32_t>::max()) return LOCMOE_ERR_SHAPE;
   return LOCMOE_OK;
 }

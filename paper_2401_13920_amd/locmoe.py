@@ -21,12 +21,14 @@ LOCMOE_F32, LOCMOE_BF16 = 0, 1
 
 EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "locmoe_capacity",
            "locmoe_workspace_bytes", "locmoe_gate", "locmoe_route", "locmoe_dispatch",
-           "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine")
+           "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine",
+           "locmoe_packed_weights_bytes", "locmoe_pack_weights")
 
 
 class locmoe_desc(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("E", C.c_int32), ("N", C.c_int32), ("h", C.c_int32),
-                ("C", C.c_int32), ("x_dtype", C.c_int32), ("relu", C.c_int32), ("alpha", C.c_float),
+                ("C", C.c_int32), ("x_dtype", C.c_int32), ("relu", C.c_int32), ("w_packed", C.c_int32),
+                ("alpha", C.c_float),
                 ("mu", C.c_float)]
 
 
@@ -64,8 +66,11 @@ def lib() -> C.CDLL:
     L.locmoe_expert_ffn_in.argtypes = [D] + [P] * 6
     L.locmoe_expert_ffn_out.argtypes = [D] + [P] * 6
     L.locmoe_combine.argtypes = [D] + [P] * 5
+    L.locmoe_packed_weights_bytes.restype = SZ
+    L.locmoe_packed_weights_bytes.argtypes = [D]
+    L.locmoe_pack_weights.argtypes = [D] + [P] * 5
     for n in EXPORTS:
-        if n not in ("locmoe_status_string", "locmoe_workspace_bytes"):
+        if n not in ("locmoe_status_string", "locmoe_workspace_bytes", "locmoe_packed_weights_bytes"):
             getattr(L, n).restype = C.c_int
     _lib = L
     return L
@@ -102,9 +107,9 @@ def _stream(stream) -> int | None:
     return stream.cuda_stream
 
 
-def make_desc(T, d, E, N, h, Cap, dtype="bf16", relu=True, alpha=0.01, mu=0.01) -> locmoe_desc:
+def make_desc(T, d, E, N, h, Cap, dtype="bf16", relu=True, alpha=0.01, mu=0.01, w_packed=False) -> locmoe_desc:
     return locmoe_desc(T, d, E, N, h, Cap, LOCMOE_BF16 if dtype == "bf16" else LOCMOE_F32, 1 if relu else 0,
-                       alpha, mu)
+                       1 if w_packed else 0, alpha, mu)
 
 
 # ---- host scalars ------------------------------------------------------------------------
@@ -160,6 +165,15 @@ def locmoe_expert_ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, stream=Non
 def locmoe_expert_ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, stream=None):
     _check(lib().locmoe_expert_ffn_out(C.byref(desc), _ptr(H_ws), _ptr(seg_off), _ptr(buf_expert), _ptr(W_out),
                                        _ptr(out), _stream(stream)))
+
+
+def locmoe_packed_weights_bytes(desc: locmoe_desc) -> int:
+    return int(lib().locmoe_packed_weights_bytes(C.byref(desc)))
+
+
+def locmoe_pack_weights(desc, W_in, W_out, W_in_packed, W_out_packed, stream=None):
+    _check(lib().locmoe_pack_weights(C.byref(desc), _ptr(W_in), _ptr(W_out), _ptr(W_in_packed), _ptr(W_out_packed),
+                                     _stream(stream)))
 
 
 def locmoe_combine(desc, out, slot, w, y, stream=None):

@@ -97,6 +97,39 @@ def check_dispatch(env, c, desc, b, x, x_dev, eid, e2n, C):
     return s, K
 
 
+def packed_desc(lm, desc):
+    """A copy of the descriptor that selects the packed-weight kernels, or None if the shape cannot."""
+    if lm.locmoe_packed_weights_bytes(desc) == 0 or desc.x_dtype != lm.LOCMOE_BF16:
+        return None
+    import copy
+    d2 = copy.copy(desc)
+    d2.w_packed = 1
+    return d2
+
+
+def pack(env, desc, W_in_dev, W_out_dev):
+    torch, lm, hz = env
+    n = lm.locmoe_packed_weights_bytes(desc)
+    assert n == W_in_dev.numel() * 2
+    Wi = torch.empty_like(W_in_dev); Wo = torch.empty_like(W_out_dev)
+    lm.locmoe_pack_weights(desc, W_in_dev, W_out_dev, Wi, Wo)
+    torch.cuda.synchronize()
+    # the documented layout, checked on a few 16-byte chunks: chunk p of block (e, nt, kt) holds row p/4,
+    # k-chunk (p%4) ^ ((row/4)%4)
+    rng = np.random.default_rng(5)
+    for W, Wp in ((W_in_dev, Wi), (W_out_dev, Wo)):
+        E, N, K = W.shape
+        flat = Wp.view(-1)
+        for _ in range(64):
+            e, nt, kt, p = (int(rng.integers(0, E)), int(rng.integers(0, N // 256)), int(rng.integers(0, K // 32)),
+                            int(rng.integers(0, 1024)))
+            row = p // 4
+            kc = (p % 4) ^ ((row // 4) % 4)
+            off = (((e * (N // 256) + nt) * (K // 32) + kt) * 1024 + p) * 8
+            assert torch.equal(flat[off:off + 8], W[e, nt * 256 + row, kt * 32 + kc * 8: kt * 32 + kc * 8 + 8])
+    return Wi, Wo
+
+
 def check_ffn(env, c, desc, b, x, s, K, W_in_dev, W_out_dev, weights, sample=None):
     """FFN on the oracle's send buffer; full compare, or only the listed buffer rows."""
     torch, lm, hz = env
@@ -107,11 +140,29 @@ def check_ffn(env, c, desc, b, x, s, K, W_in_dev, W_out_dev, weights, sample=Non
     torch.cuda.synchronize()
     if sample is None:
         ref = orc.expert_ffn(x[s["row_token"]], s["seg_off"], s["buf_expert"], weights)
-        got = hz.to_host_f32(b.out[:K])
-        assert rel_l2(got, ref) <= 1e-2
-        if K:
-            rows = np.linalg.norm(got - ref, axis=1) / (np.linalg.norm(ref, axis=1) + 1e-30)
-            assert rows.max() <= 3e-2                                        # no single row is off
+
+        def compare(out_t, H_t):
+            got = hz.to_host_f32(out_t[:K])
+            assert rel_l2(got, ref) <= 1e-2
+            if K:
+                rows = np.linalg.norm(got - ref, axis=1) / (np.linalg.norm(ref, axis=1) + 1e-30)
+                assert rows.max() <= 3e-2                                    # no single row is off
+                # the intermediate H = GeLU(W_in x), element by element: bf16 rounding + the erfc formula
+                r = int(np.argmax(np.diff(s["seg_off"])))
+                e = int(s["buf_expert"][r]); a = int(s["seg_off"][r])
+                xb = wl.round_to_storage(x[s["row_token"][a]], "bf16").astype(np.float64)
+                href = orc.gelu(weights(e)[0].astype(np.float64) @ xb)
+                hgot = hz.to_host_f32(H_t[a])
+                assert np.all(np.abs(hgot - href) <= 2.0 ** -7 * np.abs(href) + 2e-6)
+
+        compare(b.out, b.H)
+        dp = packed_desc(lm, desc)
+        if dp is not None:                                                   # same inputs through the packed-weight kernels
+            Wi, Wo = pack(env, desc, W_in_dev, W_out_dev)
+            b.out.zero_(); b.H.zero_()
+            lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out)
+            torch.cuda.synchronize()
+            compare(b.out, b.H)
         return ref
     for r in sample:
         rank = int(np.searchsorted(s["seg_off"], r, side="right") - 1)
@@ -277,8 +328,15 @@ def run_big(env, c, C, with_ffn=True):
         if z > a:
             sample += sorted({a, (a + z) // 2, z - 1, min(z - 1, a + 255), min(z - 1, a + 256)})
     check_ffn(env, c, desc, b, x, s, K, W_in, W_out, lambda e: host_w[e], sample=sample)
-    say(f"      ffn sampled rows ok: {len(sample)} rows of experts {sorted(cand)} ({time.time() - t0:.1f}s)")
-    # the chained path in the benchmark's launch configuration, y on the sampled tokens
+    say(f"      ffn (row-major weights) sampled rows ok: {len(sample)} rows of experts {sorted(cand)} "
+        f"({time.time() - t0:.1f}s)")
+    # the benchmark's launch configuration: packed weights, direct-to-LDS kernels
+    dp = packed_desc(lm, desc)
+    assert dp is not None
+    W_in, W_out = pack(env, desc, W_in, W_out)
+    desc = dp
+    check_ffn(env, c, desc, b, x, s, K, W_in, W_out, lambda e: host_w[e], sample=sample)
+    say(f"      ffn (packed weights) sampled rows ok ({time.time() - t0:.1f}s)")
     b2 = lm.alloc_buffers(desc)
     lm.forward(desc, x_dev, i32(torch, home), None, W_in, W_out, b2)
     torch.cuda.synchronize()

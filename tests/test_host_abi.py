@@ -111,6 +111,15 @@ def test_descriptor_validation_without_gpu():
     assert _status(lm.locmoe_dispatch, dsc, p, None, None, p, p, p, p, p, p, p, p, p, 1 << 20, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_expert_ffn, dsc, p, p, p, p, None, p, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    # packed weights need 256-multiples of d and h and bf16 activations
+    assert lm.locmoe_packed_weights_bytes(dsc) == 0
+    big = lm.make_desc(T=64, d=512, E=8, N=2, h=256, Cap=4)
+    assert lm.locmoe_packed_weights_bytes(big) == 8 * 512 * 256 * 2
+    assert _status(lm.locmoe_pack_weights, dsc, p, p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
+    assert _status(lm.locmoe_pack_weights, big, p, None, p, p, 0) == lm.LOCMOE_ERR_NULL
+    bad_packed = lm.make_desc(**dict(good, w_packed=True))
+    assert _status(lm.locmoe_expert_ffn_in, bad_packed, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
+    assert _status(lm.locmoe_expert_ffn_out, bad_packed, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
     zero_c = lm.make_desc(**dict(good, Cap=0))
     assert _status(lm.locmoe_combine, zero_c, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
 
