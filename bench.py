@@ -19,6 +19,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the two grouped-GEMM kernels at the bench workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (KiB per dispatch; profiles/bench_config4_kernels_and_hbm_counters.txt).  FETCH_SIZE is scaled by 2.0,
+# the factor the same counter needs for a plain 1 GiB copy in the same run; WRITE_SIZE needs none.
+PMC_KIB = {"ffn_in": (5566572.2, 814959.6), "ffn_out": (5829873.3, 203600.3)}
+FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
@@ -118,6 +124,10 @@ def main() -> int:
         hs = i32(np.roll(home, sh))
         sets.append((xs, hs, lm.alloc_buffers(desc)))
     stream = torch.cuda.current_stream()
+    # a plain copy of known size (1 GiB read + 1 GiB written): the calibration kernel for HBM byte counters
+    calib = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    calib2 = calib.clone()
+    del calib, calib2
 
     def step(k):
         xs, hs, b = sets[k % len(sets)]
@@ -175,7 +185,10 @@ def main() -> int:
     kname = "ffn_gemm_dma" if desc.w_packed else "ffn_gemm_256"
     roofline = {"bound": "mfma", "kernel": f"{kname} ({dom})", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": None, "flops_per_launch": flops, "ms_per_launch": round(ms[dom], 4)}
+                "traffic": (round((PMC_KIB[dom][0] * FETCH_FACTOR + PMC_KIB[dom][1] * WRITE_FACTOR) * 1024)
+                            if desc.w_packed and c.cfg == 4 and not args.capacity else None),
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE)",
+                "flops_per_launch": flops, "ms_per_launch": round(ms[dom], 4)}
 
     result = {
         "metric": "MoE-layer fwd tokens/sec (gate+dispatch+FFN+combine); dispatch GB/s vs HBM peak",

@@ -66,11 +66,12 @@ void launch(const void* out, const int32_t* slot, const float* w, void* y, int T
 template <bool BF16>
 void dispatch_lpr(const void* out, const int32_t* slot, const float* w, void* y, int T, int chunks,
                   hipStream_t st) {
-  if (chunks >= 256) launch<BF16, 256>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 128) launch<BF16, 128>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 64) launch<BF16, 64>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 32) launch<BF16, 32>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 16) launch<BF16, 16>(out, slot, w, y, T, chunks, st);
+  // lanes per row: every lane should own at least 4 chunks so that 4 loads are in flight before the stores
+  if (chunks >= 1024) launch<BF16, 256>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 512) launch<BF16, 128>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 256) launch<BF16, 64>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 128) launch<BF16, 32>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 64) launch<BF16, 16>(out, slot, w, y, T, chunks, st);
   else launch<BF16, 8>(out, slot, w, y, T, chunks, st);
 }
 

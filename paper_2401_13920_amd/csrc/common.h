@@ -85,7 +85,7 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? LOCMOE_OK 
 int check_desc(const locmoe_desc* d);
 
 // route / dispatch scratch layout (see workspace.cpp)
-constexpr int kRouteMaxBlocks = 256;     // upper bound of route blocks (partials per block)
+constexpr int kRouteMaxBlocks = 512;     // upper bound of route blocks (partials per block)
 constexpr int kDispatchTokensPerBlock = 1024;
 
 }  // namespace locmoe

@@ -55,18 +55,41 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int b = blockIdx.x;
 
-  // tokens per expert in earlier blocks, and in all blocks
-  for (int e = tid; e < E; e += kDispThreads) {
-    int before = 0, all = 0;
-    for (int q = 0; q < nblocks; ++q) {
-      const int c = blockcnt[(size_t)q * E + e];
-      before += q < b ? c : 0;
-      all += c;
+  // tokens per expert in earlier blocks, and in all blocks: thread (rg, e) adds the rows q = rg, rg+R, ...
+  // of the [blocks, E] count matrix (independent loads), then the R partials are added in order
+  {
+    const int R = E < kDispThreads ? kDispThreads / E : 1;  // row groups working on one chunk of experts
+    int32_t* part_before = wcnt;                             // [R][E] scratch (wcnt is zeroed afterwards)
+    int32_t* part_all = wcnt + kDispThreads;                 // R*E <= kDispThreads when R > 1
+    for (int e0 = 0; e0 < E; e0 += kDispThreads) {
+      const int e = e0 + (R > 1 ? tid % E : tid), rg = R > 1 ? tid / E : 0;
+      int before = 0, all = 0;
+      if (e < E && rg < R) {
+#pragma unroll 4
+        for (int q = rg; q < nblocks; q += R) {
+          const int c = blockcnt[(size_t)q * E + e];
+          before += q < b ? c : 0;
+          all += c;
+        }
+      }
+      if (R > 1) {
+        if (rg < R) { part_before[rg * E + e] = before; part_all[rg * E + e] = all; }
+        __syncthreads();
+        if (tid < E) {
+          before = 0; all = 0;
+          for (int q = 0; q < R; ++q) { before += part_before[q * E + tid]; all += part_all[q * E + tid]; }
+        }
+        __syncthreads();
+      }
+      const int eo = R > 1 ? tid : e;
+      if (eo < E && (R == 1 || tid < E)) {
+        off[eo] = before;
+        tot[eo] = all < C ? all : C;  // kept[e] = min(cnt[e], C)
+        node[eo] = e2n ? e2n[eo] : eo / (E / N);
+      }
     }
-    off[e] = before;
-    tot[e] = all < C ? all : C;  // kept[e] = min(cnt[e], C)
-    node[e] = e2n ? e2n[e] : e / (E / N);
   }
+  __syncthreads();
   for (int i = tid; i < kDispWaves * E; i += kDispThreads) wcnt[i] = 0;
   __syncthreads();
   // buffer order: experts sorted by (node, id)
@@ -226,7 +249,8 @@ extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int
   if (st != LOCMOE_OK) return st;
   int nbits = 0;
   while ((1 << nbits) < E) ++nbits;
-  const size_t smem = ((size_t)E * 5 + 1 + (size_t)kDispWaves * E) * 4;
+  const size_t wcnt_ints = (size_t)kDispWaves * E > 2 * (size_t)kDispThreads ? (size_t)kDispWaves * E : 2 * (size_t)kDispThreads;
+  const size_t smem = ((size_t)E * 5 + 1 + wcnt_ints) * 4;
   hipLaunchKernelGGL(dispatch_slots_kernel, dim3(nblocks), dim3(kDispThreads), smem, s, eid, e2n, blockcnt, pos,
                      slot, kept, seg_off, node_off, buf_expert, row_token, T, E, desc->N, desc->C, nblocks, nbits);
   st = launch_status();
@@ -235,11 +259,12 @@ extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int
   const long long cap = (long long)E * desc->C;
   const int rows = (int)(cap < T ? cap : T);
   const int chunks = desc->d * (desc->x_dtype == LOCMOE_BF16 ? 2 : 4) / 16;
-  if (chunks >= 256) launch_copy<256>(x, row_token, seg_off, send, E, rows, chunks, s);
-  else if (chunks >= 128) launch_copy<128>(x, row_token, seg_off, send, E, rows, chunks, s);
-  else if (chunks >= 64) launch_copy<64>(x, row_token, seg_off, send, E, rows, chunks, s);
-  else if (chunks >= 32) launch_copy<32>(x, row_token, seg_off, send, E, rows, chunks, s);
-  else if (chunks >= 16) launch_copy<16>(x, row_token, seg_off, send, E, rows, chunks, s);
+  // lanes per row: every lane should own at least 4 chunks so that 4 loads are in flight before the stores
+  if (chunks >= 1024) launch_copy<256>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 512) launch_copy<128>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 256) launch_copy<64>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 128) launch_copy<32>(x, row_token, seg_off, send, E, rows, chunks, s);
+  else if (chunks >= 64) launch_copy<16>(x, row_token, seg_off, send, E, rows, chunks, s);
   else launch_copy<8>(x, row_token, seg_off, send, E, rows, chunks, s);
   return launch_status();
 }

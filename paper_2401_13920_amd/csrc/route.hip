@@ -78,17 +78,26 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
 
   const int tok0 = blockIdx.x * tokens_per_block;
   const int tok1 = min(T, tok0 + tokens_per_block);
-  for (int base = tok0; base < tok1; base += G * kTokPerGroup) {
-    float v[kTokPerGroup][EPL];
+  // the loads of the next batch of tokens are issued before the current batch is reduced
+  float v[kTokPerGroup][EPL], nxt[kTokPerGroup][EPL];
+  auto load_batch = [&](float (&dst)[kTokPerGroup][EPL], int base) {
 #pragma unroll
     for (int t = 0; t < kTokPerGroup; ++t) {
       const int m = base + t * G + grp;
 #pragma unroll
       for (int k = 0; k < EPL; ++k) {
         const int i = j + k * S;
-        v[t][k] = (m < tok1 && i < E) ? g[(size_t)m * E + i] : -INFINITY;
+        dst[t][k] = (m < tok1 && i < E) ? g[(size_t)m * E + i] : -INFINITY;
       }
     }
+  };
+  load_batch(nxt, tok0);
+  for (int base = tok0; base < tok1; base += G * kTokPerGroup) {
+#pragma unroll
+    for (int t = 0; t < kTokPerGroup; ++t)
+#pragma unroll
+      for (int k = 0; k < EPL; ++k) v[t][k] = nxt[t][k];
+    load_batch(nxt, base + G * kTokPerGroup);
 #pragma unroll
     for (int t = 0; t < kTokPerGroup; ++t) {
       const int m = base + t * G + grp;
@@ -179,11 +188,13 @@ __global__ __launch_bounds__(kFinThreads) void route_finalize_kernel(
     const int e = tid % E, rb = tid / E;
     int32_t ci = 0;
     double ps = 0.0;
-    if (rb < R)
+    if (rb < R) {
+#pragma unroll 8
       for (int b = rb; b < nb; b += R) {
         ci += r.cnt[(size_t)b * E + e];
         ps += (double)r.psum[(size_t)b * E + e];
       }
+    }
     ipart[tid] = ci;
     dpart[tid] = ps;
     __syncthreads();
@@ -205,8 +216,10 @@ __global__ __launch_bounds__(kFinThreads) void route_finalize_kernel(
     const int R = kFinThreads / N;
     const int nu = tid % N, rb = tid / N;
     int32_t hi = 0;
-    if (rb < R)
+    if (rb < R) {
+#pragma unroll 8
       for (int b = rb; b < nb; b += R) hi += r.home[(size_t)b * N + nu];
+    }
     if (rb < R && hi) atomicAdd(&s_home[nu], hi);
     if (tid < E) atomicAdd(&s_pernode[e2n ? e2n[tid] : tid / (E / N)], 1);
     for (int b = tid; b < nb; b += kFinThreads) local += r.local[b];

@@ -127,6 +127,6 @@ def test_descriptor_validation_without_gpu():
 def test_workspace_size_covers_both_users():
     for c in wl.CONFIGS.values():
         d = lm.make_desc(c.T, c.d, c.E, c.N, c.h, c.C, c.dtype)
-        need_route = 256 * (c.E * 8 + c.N * 4 + 4)
+        need_route = 512 * (c.E * 8 + c.N * 4 + 4)
         need_disp = -(-c.T // 1024) * c.E * 4
         assert lm.locmoe_workspace_bytes(d) >= max(need_route, need_disp)
