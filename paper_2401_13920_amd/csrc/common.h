@@ -32,8 +32,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   __bf16 b = (__bf16)f;
   return __builtin_bit_cast(uint16_t, b);
 }
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+// two floats -> two bf16 in one register (one v_cvt_pk_bf16_f32), lo in bits 0..15
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+  const f32x2 v = {lo, hi};
+  const bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
 }
 
 // Sum of the 8 bf16 values held in a 16-byte vector, as a fixed fp32 tree.
