@@ -246,7 +246,7 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 // ---------------------------------------------------------------------------------------------
 // DMA kernel: 256x256 tile, BK = 32, 8 waves (2 along m x 4 along n, 128x64 per wave), kStages LDS
 // stages of 32 KiB filled by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers,
-// no ds_write), so up to two stages (64 KiB per CU) are in flight while two are being consumed.
+// no ds_write), so up to three stages (96 KiB per CU) are in flight while two are being consumed.
 //
 // LDS image of a stage: A rows then B rows, 64 bytes (4 chunks of 8 bf16) per row, chunk kc of row r
 // in slot kc ^ (r/4 mod 4): 16 lanes reading 16 consecutive rows touch all 64 banks once.  A
@@ -256,8 +256,8 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 //
 // The compiler does not know about these loads (inline asm), so the vmcnt accounting is explicit:
 // every wave issues kLoadsPerStage loads per stage, loads complete in order, and nothing else in
-// the K loop uses vmcnt.  Pipeline invariant at the top of iteration kt: stages kt and kt+1 are
-// complete and visible; F[0] holds the fragments of (kt, k-step 0).
+// the K loop uses vmcnt.  Pipeline invariant at the top of iteration kt: stage kt is complete and
+// visible and its first fragments are in registers; tiles kt+1 .. kt+kStages-2 are in flight.
 //
 // Rows of the tile are owned in interleaved 16-row subtiles (wave row wm owns subtiles wm, wm+2,
 // ...), so a ragged tile skips MFMAs evenly across waves, at 32-row granularity overall.
@@ -368,10 +368,10 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
 #pragma unroll
       for (int ni = 0; ni < 4; ++ni) acc[ni][j] = mfma16_bf16(fw[C][ni], fa_lo[j], acc[ni][j]);
     __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<kLoadsPerStage * (kStages - 4)>();  // tile kt+2 has landed (this wave's share)
-    __syncthreads();                // stage of kt+2 complete for everybody; nobody reads the stage of kt-1 any more
-    issue(kt + kStages - 1, fill);  // refill the stage tile kt-1 was in
-    load_w(n_, nxt);                // complete since the previous barrier (for kt+1 == KT: a clamped copy, unused)
+    wait_vmcnt<kLoadsPerStage * (kStages - 3)>();  // tile kt+1 has landed (this wave's share)
+    __syncthreads();                // stage of kt+1 complete for everybody; nobody reads the stage of kt-1 any more
+    issue(kt + kStages - 1, fill);  // refill the stage tile kt-1 was in: kStages-2 stages are now in flight
+    load_w(n_, nxt);                // (for kt+1 == KT: a clamped copy of the last tile, unused)
     load_lo(nxt);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -385,7 +385,7 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
 
 #pragma unroll
   for (int t = 0; t < kStages - 1; ++t) issue(t, t);
-  wait_vmcnt<kLoadsPerStage * (kStages - 3)>();  // tiles 0 and 1 have landed (this wave's share)
+  wait_vmcnt<kLoadsPerStage * (kStages - 2)>();  // tile 0 has landed (this wave's share)
   __syncthreads();                               // ... and everybody's
   load_w(I0{}, 0);
   load_lo(0);

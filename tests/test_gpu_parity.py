@@ -267,6 +267,16 @@ def test_ragged_token_counts_and_wide_experts(env):
     run_full(env, wl.small_config(T=300, d=96, E=8, N=2, h=24, dtype="f32"), 20)
 
 
+def test_expert_count_limits(env):
+    # the largest expert count the ABI allows: 16 experts per lane in the router, 1-wide GrAP blocks
+    run_full(env, wl.small_config(T=700, d=1024, E=1024, N=32, h=8, clusters=7), 2)
+    # one node, every expert local; capacity of a single row
+    run_full(env, wl.small_config(T=257, d=64, E=64, N=1, h=16, clusters=3), 1)
+    # more nodes than the default map could give evenly is rejected on the host; a free-form map works
+    e2n = (np.arange(12) * 5 % 7).astype(np.int32)
+    run_full(env, wl.small_config(T=513, d=96, E=12, N=7, h=24, clusters=4), 11, e2n=e2n)
+
+
 def test_tuned_gemm_tiles_with_ragged_segments(env):
     # d, h multiples of the tuned tile; capacity spans several 256-row tiles with ragged tails
     run_full(env, wl.small_config(T=4096, d=256, E=4, N=2, h=512, clusters=3), 700)
