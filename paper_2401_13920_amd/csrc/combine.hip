@@ -26,7 +26,9 @@ __device__ __forceinline__ uint4 scale16(const uint4& v, float w) {
   return r;
 }
 
-// LPR lanes share one token row of `chunks` 16-byte vectors.
+// LPR lanes share one token row of `chunks` 16-byte vectors; one block per group of rows.  Measured at the
+// headline shape (8 KiB rows): many lanes per row with one or two chunks each beats fewer lanes with deeper
+// unrolling, and a grid-stride loop is slower than one short-lived block per row group.
 template <bool BF16, int LPR>
 __global__ __launch_bounds__(kCombThreads) void combine_kernel(const uint4* __restrict__ out,
                                                                const int32_t* __restrict__ slot,
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(kCombThreads) void combine_kernel(const uint4* __re
 #pragma unroll
     for (int u = 0; u < U; ++u) nt_store16(scale16<BF16>(v[u], wm), dst + c + u * LPR);
   }
-  for (; c < chunks; c += LPR) dst[c] = scale16<BF16>(src[c], wm);
+  for (; c < chunks; c += LPR) nt_store16(scale16<BF16>(nt_load16(src + c), wm), dst + c);
 }
 
 template <bool BF16, int LPR>
@@ -66,12 +68,11 @@ void launch(const void* out, const int32_t* slot, const float* w, void* y, int T
 template <bool BF16>
 void dispatch_lpr(const void* out, const int32_t* slot, const float* w, void* y, int T, int chunks,
                   hipStream_t st) {
-  // lanes per row: every lane should own at least 4 chunks so that 4 loads are in flight before the stores
-  if (chunks >= 1024) launch<BF16, 256>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 512) launch<BF16, 128>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 256) launch<BF16, 64>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 128) launch<BF16, 32>(out, slot, w, y, T, chunks, st);
-  else if (chunks >= 64) launch<BF16, 16>(out, slot, w, y, T, chunks, st);
+  if (chunks >= 256) launch<BF16, 256>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 128) launch<BF16, 128>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 64) launch<BF16, 64>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 32) launch<BF16, 32>(out, slot, w, y, T, chunks, st);
+  else if (chunks >= 16) launch<BF16, 16>(out, slot, w, y, T, chunks, st);
   else launch<BF16, 8>(out, slot, w, y, T, chunks, st);
 }
 

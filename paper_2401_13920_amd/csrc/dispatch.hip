@@ -54,6 +54,14 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
   int32_t* wcnt = seg + E + 1;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int b = blockIdx.x;
+  // this lane's tokens (wave-contiguous), fetched first so that the loads overlap the prefix work below
+  const int wbase = b * kDispatchTokensPerBlock + wave * kTokPerWave;
+  int my_e[kIter], my_p[kIter];
+#pragma unroll
+  for (int k = 0; k < kIter; ++k) {
+    const int m = wbase + k * kWave + lane;
+    my_e[k] = m < T ? eid[m] : -1;
+  }
 
   // tokens per expert in earlier blocks, and in all blocks: thread (rg, e) adds the rows q = rg, rg+R, ...
   // of the [blocks, E] count matrix (independent loads), then the R partials are added in order
@@ -138,14 +146,11 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
   }
 
   // rank of each token among the block's earlier tokens of the same expert
-  const int wbase = b * kDispatchTokensPerBlock + wave * kTokPerWave;
-  int my_e[kIter], my_p[kIter];
   int32_t* wc = wcnt + wave * E;
 #pragma unroll
   for (int k = 0; k < kIter; ++k) {
-    const int m = wbase + k * kWave + lane;
-    const bool valid = m < T;
-    const int e = valid ? eid[m] : 0;
+    const bool valid = my_e[k] >= 0;
+    const int e = valid ? my_e[k] : 0;
     unsigned long long peers = __ballot(valid);
     for (int bit = 0; bit < nbits; ++bit) {
       const bool set = (e >> bit) & 1;
@@ -159,7 +164,6 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
     wave_sync();
     if (valid && before == 0) wc[e] = p + __popcll(peers);  // ... then each group's first lane advances it
     wave_sync();
-    my_e[k] = valid ? e : -1;
     my_p[k] = p;
   }
   __syncthreads();
@@ -191,37 +195,49 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
   }
 }
 
-// send[r,:] = x[row_token[r],:].  A row is `chunks` 16-byte vectors; LPR lanes share a row.
+// send[r,:] = x[row_token[r],:].  A row is `chunks` 16-byte vectors; LPR lanes share a row.  Blocks walk the
+// K kept rows with a grid stride; the token index of the next row is fetched before the current row is
+// copied, so the index -> row dependency is off the critical path.
+constexpr int kCopyBlocksPerCu = 8, kCus = 256;
+
 template <int LPR>
 __global__ __launch_bounds__(kDispThreads) void dispatch_copy_kernel(const uint4* __restrict__ x,
                                                                      const int32_t* __restrict__ row_token,
                                                                      const int32_t* __restrict__ seg_off,
                                                                      uint4* __restrict__ send, int E, int chunks) {
   constexpr int RPB = kDispThreads / LPR;
-  const int K = seg_off[E];
-  const int r = blockIdx.x * RPB + threadIdx.x / LPR;
-  if (r >= K) return;
-  const int l = threadIdx.x % LPR;
-  const uint4* src = x + (size_t)row_token[r] * chunks;
-  uint4* dst = send + (size_t)r * chunks;
   constexpr int U = 4;
-  int c = l;
-  for (; c + (U - 1) * LPR < chunks; c += U * LPR) {
-    uint4 v[U];
+  const int K = seg_off[E];
+  const int l = threadIdx.x % LPR;
+  const int stride = gridDim.x * RPB;
+  int r = blockIdx.x * RPB + threadIdx.x / LPR;
+  int tok = r < K ? row_token[r] : 0;
+  while (r < K) {
+    const int rn = r + stride;
+    const int tokn = rn < K ? row_token[rn] : 0;
+    const uint4* src = x + (size_t)tok * chunks;
+    uint4* dst = send + (size_t)r * chunks;
+    int c = l;
+    for (; c + (U - 1) * LPR < chunks; c += U * LPR) {
+      uint4 v[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = nt_load16(src + c + u * LPR);
+      for (int u = 0; u < U; ++u) v[u] = nt_load16(src + c + u * LPR);
 #pragma unroll
-    for (int u = 0; u < U; ++u) nt_store16(v[u], dst + c + u * LPR);
+      for (int u = 0; u < U; ++u) dst[c + u * LPR] = v[u];  // plain stores: the FFN re-reads send right away
+    }
+    for (; c < chunks; c += LPR) dst[c] = nt_load16(src + c);
+    r = rn;
+    tok = tokn;
   }
-  for (; c < chunks; c += LPR) dst[c] = src[c];
 }
 
 template <int LPR>
 void launch_copy(const void* x, const int32_t* row_token, const int32_t* seg_off, void* send, int E, int rows,
                  int chunks, hipStream_t st) {
   constexpr int RPB = kDispThreads / LPR;
-  hipLaunchKernelGGL((dispatch_copy_kernel<LPR>), dim3(ceil_div(rows, RPB)), dim3(kDispThreads), 0, st,
-                     (const uint4*)x, row_token, seg_off, (uint4*)send, E, chunks);
+  const int blocks = min(ceil_div(rows, RPB), kCus * kCopyBlocksPerCu);
+  hipLaunchKernelGGL((dispatch_copy_kernel<LPR>), dim3(blocks), dim3(kDispThreads), 0, st, (const uint4*)x,
+                     row_token, seg_off, (uint4*)send, E, chunks);
 }
 
 }  // namespace
