@@ -135,7 +135,7 @@ int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* 
  * locmoe_packed_weights_bytes returns the size of EACH packed tensor (E*h*d*2 bytes), or 0 when the
  * shape cannot be packed.  Packed layout: for expert e, 256-row tile nt and 32-column step kt, a
  * 16 KiB block at ((e*NT + nt)*KT + kt)*16 KiB whose 16-byte chunk p holds row r = p/4 of the tile,
- * columns 8*c .. 8*c+7 of the step with c = (p%4) ^ ((r/4)%4) - the LDS image the kernel consumes.
+ * columns 8*c .. 8*c+7 of the step with c = (p%4) ^ ((r/2)%4) - the LDS image the kernel consumes.
  * With desc->w_packed = 1 the three expert_ffn entry points take the packed tensors in place of
  * W_in / W_out (LOCMOE_ERR_ARG if the shape or dtype cannot use them); results are the same
  * to rounding order.  W_in [E,h,d], W_out [E,d,h] device bf16 (read); packed tensors device (written). */

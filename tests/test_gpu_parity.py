@@ -115,7 +115,7 @@ def pack(env, desc, W_in_dev, W_out_dev):
     lm.locmoe_pack_weights(desc, W_in_dev, W_out_dev, Wi, Wo)
     torch.cuda.synchronize()
     # the documented layout, checked on a few 16-byte chunks: chunk p of block (e, nt, kt) holds row p/4,
-    # k-chunk (p%4) ^ ((row/4)%4)
+    # k-chunk (p%4) ^ ((row/2)%4)
     rng = np.random.default_rng(5)
     for W, Wp in ((W_in_dev, Wi), (W_out_dev, Wo)):
         E, N, K = W.shape
@@ -124,7 +124,7 @@ def pack(env, desc, W_in_dev, W_out_dev):
             e, nt, kt, p = (int(rng.integers(0, E)), int(rng.integers(0, N // 256)), int(rng.integers(0, K // 32)),
                             int(rng.integers(0, 1024)))
             row = p // 4
-            kc = (p % 4) ^ ((row // 4) % 4)
+            kc = (p % 4) ^ ((row // 2) % 4)
             off = (((e * (N // 256) + nt) * (K // 32) + kt) * 1024 + p) * 8
             assert torch.equal(flat[off:off + 8], W[e, nt * 256 + row, kt * 32 + kc * 8: kt * 32 + kc * 8 + 8])
     return Wi, Wo
