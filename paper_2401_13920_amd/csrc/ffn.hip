@@ -275,7 +275,8 @@ constexpr int kPackBlock = kBN * kDmaBK * 2;           // 16 KiB: one packed wei
 typedef const char __attribute__((address_space(3))) * lds_cptr;
 
 // One wave-wide 1 KiB copy global -> LDS: lane l reads 16 bytes at sbase + voff and they land at
-// LDS byte address lds_base + 16 l (M0 carries the wave-uniform LDS base).
+// LDS byte address lds_base + 16 l (M0 carries the wave-uniform LDS base).  Default cache policy: nt, sc1
+// and sc0 sc1 on the weight stream all measured equal or slower.
 __device__ __forceinline__ void dma_1k(const void* sbase, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase),
                "s"(lds_base)
@@ -416,17 +417,47 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
                                                             uint16_t* __restrict__ Cout,
                                                             const int32_t* __restrict__ seg_off,
                                                             const int32_t* __restrict__ buf_expert, int Kdim,
-                                                            int Ndim, int MT, int NT, int total) {
+                                                            int Ndim, int MT, int NT, int E) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Which tile.  Work-groups with ids congruent mod 8 run on one XCD (one L2); XCD x walks the segments
+  // whose rank in descending order of row count is congruent to x, largest first, all tiles of a segment
+  // together with the m-tiles that share a weight tile adjacent.  Long tiles first means the short tiles
+  // of ragged segments fill the last round instead of leaving compute units idle (7.3 tiles per CU in the
+  // second GEMM of the headline shape).  The order is recomputed by every work-group from seg_off
+  // (E <= 1024 integers, in LDS that the pipeline overwrites afterwards).
   const int id = blockIdx.x;
-  const int lin = (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
-  const int mt = lin % MT, nt = (lin / MT) % NT, r = lin / (MT * NT);
+  const int tpe = MT * NT;  // tiles per segment
+  int within, r;
+  if (E % 8 == 0) {
+    const int xcd = id & 7, j = id >> 3;
+    const int want = (j / tpe) * 8 + xcd;  // rank in descending order of rows
+    within = j % tpe;
+    int32_t* s_seg = (int32_t*)smem;       // [E+1] then the pick
+    for (int t = tid; t <= E; t += kDmaThreads) s_seg[t] = seg_off[t];
+    __syncthreads();
+    for (int t = tid; t < E; t += kDmaThreads) {
+      const int mine = s_seg[t + 1] - s_seg[t];
+      int rank = 0;
+      for (int q = 0; q < E; ++q) {
+        const int other = s_seg[q + 1] - s_seg[q];
+        rank += (other > mine || (other == mine && q < t)) ? 1 : 0;
+      }
+      if (rank == want) s_seg[E + 1] = t;
+    }
+    __syncthreads();
+    r = s_seg[E + 1];
+    __syncthreads();  // everybody has read the pick before the first stage overwrites this memory
+  } else {
+    within = id % tpe;
+    r = id / tpe;
+  }
+  const int mt = within % MT, nt = within / MT;
   const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
   const int m0 = mt * kBM;
   if (m0 >= rows) return;
   const int e = buf_expert[r];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int rows_left = rows - m0;
   const char* Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
@@ -492,7 +523,7 @@ int launch_dma(const void* A, const void* Wp, void* C, const int32_t* seg_off, c
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
     return LOCMOE_ERR_HIP;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
-                     (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT, (int)total);
+                     (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT, E);
   return launch_status();
 }
 
