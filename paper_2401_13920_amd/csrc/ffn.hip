@@ -244,33 +244,37 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 
 
 // ---------------------------------------------------------------------------------------------
-// DMA kernel: 256x256 tile, BK = 32, 8 waves (2 along m x 4 along n, 128x64 per wave), kStages LDS
-// stages of 32 KiB filled by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers,
-// no ds_write), so up to three stages (96 KiB per CU) are in flight while two are being consumed.
+// DMA kernel: 256x256 tile, k-steps of 32, 8 waves (2 along m x 4 along n, 128x64 per wave).  Both
+// operands reach LDS by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers, no
+// ds_write), in two rings that fill all 160 KiB of a CU:
+//   weights      4 slots x 16 KiB, one k-step each (256 rows x 64 B), from the packed layout: a
+//                work-group's weight stream is one contiguous run of 16 KiB blocks;
+//   activations  3 slots x 32 KiB, two k-steps each (256 rows x 128 B): rows are fetched as whole
+//                128-byte lines.  With 64-byte row segments every line was requested in two
+//                consecutive k-steps, and the per-CU vector-memory path is what bounds this kernel
+//                (measured: +5 % from whole lines alone).
 //
-// LDS image of a stage: A rows then B rows, 64 bytes (4 chunks of 8 bf16) per row, chunk kc of row r
-// in slot kc ^ (r/2 mod 4).  For the 16x16x32 fragment read (lane l: row l%16, chunk l/16) this slot
-// function measured conflict-free (166 B/clk/CU in a read-only loop) while kc ^ (r/4 mod 4), kc ^ (r mod 4)
-// and no swizzle all measured about 118 B/clk/CU.  A
-// direct-to-LDS load writes lane l's 16 bytes at base + 16 l, so the image is produced by choosing
-// which global chunk each lane fetches; packed weights are stored as that image already, which
-// makes the weight stream of a work-group one contiguous run of 16 KiB blocks.
+// A direct-to-LDS load writes lane l's 16 bytes at base + 16 l, so the LDS image is produced by
+// choosing which global chunk each lane fetches.  Slot functions (measured conflict-free for the
+// 16x16x32 fragment read, lane l: row l%16, chunk l/16): 64-byte weight rows: chunk ^ (row/2 mod 4);
+// 128-byte activation rows: chunk ^ (row/2 mod 8).
 //
 // The compiler does not know about these loads (inline asm), so the vmcnt accounting is explicit:
-// every wave issues kLoadsPerStage loads per stage, loads complete in order, and nothing else in
-// the K loop uses vmcnt.  Pipeline invariant at the top of iteration kt: stage kt is complete and
-// visible and its first fragments are in registers; tiles kt+1 .. kt+kStages-2 are in flight.
+// loads complete in order and nothing else in the K loop uses vmcnt.  Per wave, k-step kt issues
+// the 2 weight loads of step kt+3 and, when kt is even, the 4 activation loads of double step
+// kt/2+2.  At the barrier of step kt the weights of kt+1 (and, for odd kt, the activations of double
+// step (kt+1)/2) must have landed; everything issued after them is 6 loads, hence vmcnt(6).
 //
 // Rows of the tile are owned in interleaved 16-row subtiles (wave row wm owns subtiles wm, wm+2,
 // ...), so a ragged tile skips MFMAs evenly across waves, at 32-row granularity overall.
 // ---------------------------------------------------------------------------------------------
 constexpr int kDmaBK = 32;
 constexpr int kDmaThreads = 512;
-constexpr int kDmaStage = (kBM + kBN) * kDmaBK * 2;  // 32 KiB
-constexpr int kStages = 5;
-constexpr int kDmaSmem = kStages * kDmaStage;         // 160 KiB: the whole LDS of a CU
-constexpr int kLoadsPerStage = 4;                      // per wave: 2 A blocks + 2 B blocks of 1 KiB
-constexpr int kPackBlock = kBN * kDmaBK * 2;           // 16 KiB: one packed weight block
+constexpr int kWSlots = 4, kWSlotBytes = kBN * kDmaBK * 2;     // 4 x 16 KiB
+constexpr int kASlots = 3, kASlotBytes = kBM * kDmaBK * 2 * 2;  // 3 x 32 KiB
+constexpr int kWRing = kASlots * kASlotBytes;                   // weights ring starts after the activations ring
+constexpr int kDmaSmem = kWRing + kWSlots * kWSlotBytes;        // 160 KiB: the whole LDS of a CU
+constexpr int kPackBlock = kWSlotBytes;                         // 16 KiB: one packed weight block
 
 typedef const char __attribute__((address_space(3))) * lds_cptr;
 
@@ -291,14 +295,13 @@ __device__ __forceinline__ f32x4 mfma16_bf16(const bf16x8& a, const bf16x8& b, c
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole 32-wide stage of a 16x16 output
-// tile, so a stage is a single k-step and lane l always reads LDS chunk l/16 of its rows.  Measured on
-// this part with random bf16 operands, this shape sustains about 1.97 PFLOP/s against 1.47 PFLOP/s
-// for the 32x32x16 shape (the wider accumulator path costs clocks under power management); LDS bytes per
-// flop are identical for the two shapes at this wave tile.
+// The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole 32-wide k-step of a 16x16 output
+// tile, and lane l always reads LDS chunk l/16 of its rows.  Measured on this part with random bf16
+// operands, this shape sustains about 1.97 PFLOP/s against 1.47 PFLOP/s for the 32x32x16 shape (clock
+// management); LDS bytes per flop are identical for the two shapes at this wave tile.
 template <int NJ, bool GELU>
 __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const char* __restrict__ Wbase,
-                                         uint16_t* __restrict__ Cout, uint32_t lds0, uint32_t offA0, uint32_t offA1,
+                                         uint16_t* __restrict__ Cout, uint32_t lds0, const uint32_t (&offA)[4],
                                          uint32_t offB0, uint32_t offB1, int KT, int wm, int wn, int lane, int wave,
                                          int rows_left, size_t crow0, int ldc, int n_base) {
   // NJ = live 16-row activation tiles of this wave
@@ -306,17 +309,19 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
   constexpr int NHI = NJ - NLO;               // second group (0 for short tiles)
   const int kq = lane >> 4, l16 = lane & 15;
   lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
-  // tile j of this wave: rows (2 j + wm)*16 .. +16 of the work-group tile (interleaved over the two wave rows)
-  int a_addr[8], b_addr[4];
+  // tile j of this wave: rows (2 j + wm)*16 .. +16 of the work-group tile (interleaved over the two wave rows);
+  // a_addr[half][j]: byte offset inside an activation slot for the even / odd k-step of a double step
+  int a_addr[2][8], b_addr[4];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int r = (2 * j + wm) * 16 + l16;
-    a_addr[j] = r * 64 + ((kq ^ ((r >> 1) & 3)) << 4);
+    a_addr[0][j] = r * 128 + ((kq ^ ((r >> 1) & 7)) << 4);
+    a_addr[1][j] = r * 128 + (((4 + kq) ^ ((r >> 1) & 7)) << 4);
   }
 #pragma unroll
   for (int ni = 0; ni < 4; ++ni) {
     const int r = wn * 64 + ni * 16 + l16;
-    b_addr[ni] = kBM * 64 + r * 64 + ((kq ^ ((r >> 1) & 3)) << 4);
+    b_addr[ni] = kWRing + r * 64 + ((kq ^ ((r >> 1) & 3)) << 4);
   }
   f32x4 acc[4][8];
 #pragma unroll
@@ -324,75 +329,90 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[ni][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // Tile t (clamped to the last one: the tail prefetches are redundant and never consumed) into
-  // LDS stage `stage`.  This wave copies A blocks {wave, wave+8} and B blocks {wave, wave+8}.
-  auto issue = [&](int t, int stage) {
-    const int kk = min(t, KT - 1);
-    const uint32_t st = lds0 + (uint32_t)stage * kDmaStage;
-    const char* ab = Abase + (size_t)kk * (kDmaBK * 2);
-    const char* wb = Wbase + (size_t)kk * kPackBlock;
-    dma_1k(ab, offA0, st + wave * 1024);
-    dma_1k(ab, offA1, st + (wave + 8) * 1024);
-    dma_1k(wb, offB0, st + kBM * 64 + wave * 1024);
-    dma_1k(wb, offB1, st + kBM * 64 + (wave + 8) * 1024);
+  const int KD = KT >> 1;  // double steps (KT is even)
+  // weights of k-step t (clamped to the last: tail prefetches are redundant, never consumed) into slot `slot`;
+  // this wave copies blocks {wave, wave+8} of 16
+  auto issue_w = [&](int t, int slot) {
+    const char* wb = Wbase + (size_t)min(t, KT - 1) * kPackBlock;
+    const uint32_t st = lds0 + kWRing + (uint32_t)slot * kWSlotBytes;
+    dma_1k(wb, offB0, st + wave * 1024);
+    dma_1k(wb, offB1, st + (wave + 8) * 1024);
+  };
+  // activations of double step D (clamped) into slot `slot`; this wave copies blocks {wave, wave+8, +16, +24}
+  // of 32, a block being 8 rows x 128 B
+  auto issue_a = [&](int D, int slot) {
+    const char* ab = Abase + (size_t)min(D, KD - 1) * (kDmaBK * 4);
+    const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma_1k(ab, offA[j], st + (wave + 8 * j) * 1024);
   };
   bf16x8 fw[2][4], fa_lo[4], fa_hi[4];
-  auto load_w = [&](auto buf, int stage) {
+  auto load_w = [&](auto buf, int wslot) {
     constexpr int B = decltype(buf)::value;
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni)
-      fw[B][ni] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)stage * kDmaStage + b_addr[ni]);
+      fw[B][ni] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)wslot * kWSlotBytes + b_addr[ni]);
   };
-  auto load_lo = [&](int stage) {
+  auto load_lo = [&](auto half, int aslot) {
+    constexpr int H = decltype(half)::value;
 #pragma unroll
     for (int j = 0; j < NLO; ++j)
-      fa_lo[j] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)stage * kDmaStage + a_addr[j]);
+      fa_lo[j] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)aslot * kASlotBytes + a_addr[H][j]);
   };
-  auto load_hi = [&](int stage) {
+  auto load_hi = [&](auto half, int aslot) {
+    constexpr int H = decltype(half)::value;
 #pragma unroll
     for (int j = 0; j < NHI; ++j)
-      fa_hi[j] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)stage * kDmaStage + a_addr[4 + j]);
+      fa_hi[j] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)aslot * kASlotBytes + a_addr[H][4 + j]);
   };
-  auto next_stage = [](int s) { return s + 1 == kStages ? 0 : s + 1; };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
-  int cur = 0, fill = kStages - 1;  // stage of tile kt; stage that tile kt + kStages - 1 goes to
+  int wcur = 0, wfill = 3;  // weight slot of k-step kt; slot that k-step kt+3 goes to
+  int acur = 0, afill = 2;  // activation slot of double step kt/2; slot that double step kt/2+2 goes to
 
-  // One stage.  On entry fw[C] and fa_lo hold the fragments of stage `cur`; on exit fw[1-C] and fa_lo hold
-  // those of the next stage.  The scheduling barriers keep every fragment read ahead of the MFMAs that
+  // One k-step; PAR = kt % 2.  On entry fw[PAR] and fa_lo hold the fragments of step kt; on exit fw[1-PAR] and
+  // fa_lo hold those of step kt+1.  The scheduling barriers keep every fragment read ahead of the MFMAs that
   // run while it is in flight.
-  auto step = [&](auto c_, auto n_, int kt) {
-    constexpr int C = decltype(c_)::value;
-    const int nxt = next_stage(cur);
-    load_hi(cur);
+  auto step = [&](auto par_, auto npar_, int kt) {
+    constexpr int PAR = decltype(par_)::value;
+    const int wnxt = wcur + 1 == kWSlots ? 0 : wcur + 1;
+    const int anxt = PAR == 0 ? acur : (acur + 1 == kASlots ? 0 : acur + 1);  // slot of step kt+1's activations
+    load_hi(par_, acur);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < NLO; ++j)
 #pragma unroll
-      for (int ni = 0; ni < 4; ++ni) acc[ni][j] = mfma16_bf16(fw[C][ni], fa_lo[j], acc[ni][j]);
+      for (int ni = 0; ni < 4; ++ni) acc[ni][j] = mfma16_bf16(fw[PAR][ni], fa_lo[j], acc[ni][j]);
     __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<kLoadsPerStage * (kStages - 3)>();  // tile kt+1 has landed (this wave's share)
-    __syncthreads();                // stage of kt+1 complete for everybody; nobody reads the stage of kt-1 any more
-    issue(kt + kStages - 1, fill);  // refill the stage tile kt-1 was in: kStages-2 stages are now in flight
-    load_w(n_, nxt);                // (for kt+1 == KT: a clamped copy of the last tile, unused)
-    load_lo(nxt);
+    wait_vmcnt<6>();   // weights of kt+1 (and, for odd kt, activations of double step (kt+1)/2) have landed
+    __syncthreads();   // ... for everybody; nobody reads weight slot kt-1 or, for even kt, activation slot kt/2-1
+    issue_w(kt + 3, wfill);
+    if (PAR == 0) issue_a((kt >> 1) + 2, afill);
+    load_w(npar_, wnxt);       // (for kt+1 == KT: clamped copies of the last step, unused)
+    load_lo(npar_, anxt);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < NHI; ++j)
 #pragma unroll
-      for (int ni = 0; ni < 4; ++ni) acc[ni][4 + j] = mfma16_bf16(fw[C][ni], fa_hi[j], acc[ni][4 + j]);
+      for (int ni = 0; ni < 4; ++ni) acc[ni][4 + j] = mfma16_bf16(fw[PAR][ni], fa_hi[j], acc[ni][4 + j]);
     __builtin_amdgcn_sched_barrier(0);
-    cur = nxt;
-    fill = next_stage(fill);
+    wcur = wnxt;
+    wfill = wfill + 1 == kWSlots ? 0 : wfill + 1;
+    if (PAR == 0) afill = afill + 1 == kASlots ? 0 : afill + 1;
+    acur = anxt;
   };
 
-#pragma unroll
-  for (int t = 0; t < kStages - 1; ++t) issue(t, t);
-  wait_vmcnt<kLoadsPerStage * (kStages - 2)>();  // tile 0 has landed (this wave's share)
-  __syncthreads();                               // ... and everybody's
+  // prologue, in the steady state's issue order: A(0) W(0) W(1) A(1) W(2)
+  issue_a(0, 0);
+  issue_w(0, 0);
+  issue_w(1, 1);
+  issue_a(1, 1);
+  issue_w(2, 2);
+  wait_vmcnt<8>();  // A(0) and W(0) have landed (this wave's share); W(1) A(1) W(2) = 8 loads may be in flight
+  __syncthreads();  // ... and everybody's
   load_w(I0{}, 0);
-  load_lo(0);
-  for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K is a multiple of 256)
+  load_lo(I0{}, 0);
+  for (int kt = 0; kt < KT; kt += 2) {
     step(I0{}, I1{}, kt);
     step(I1{}, I0{}, kt + 1);
   }
@@ -462,13 +482,13 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   const int rows_left = rows - m0;
   const char* Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
   const char* Wbase = (const char*)(Wp + ((size_t)e * Ndim + (size_t)nt * kBN) * (size_t)Kdim);
-  // lane l of the copy of row block b: row 16 b + l/4, LDS slot l%4 receives chunk (l%4) ^ (row/2 mod 4).
-  // Rows past the segment's end re-read its last row (results masked at the store).
-  uint32_t offA[2];
+  // activations: lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS slot l%8 receives chunk
+  // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
+  uint32_t offA[4];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int row = 16 * (wave + 8 * j) + (lane >> 2);
-    const int kc = (lane & 3) ^ ((row >> 1) & 3);
+  for (int j = 0; j < 4; ++j) {
+    const int row = 8 * (wave + 8 * j) + (lane >> 3);
+    const int kc = (lane & 7) ^ ((row >> 1) & 7);
     offA[j] = (uint32_t)min(row, rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
   }
   const uint32_t offB0 = (uint32_t)(wave * 1024 + lane * 16), offB1 = offB0 + 8 * 1024;
@@ -479,8 +499,8 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   const size_t crow0 = (size_t)seg0 + m0;
   const int n_base = nt * kBN;
 #define LOCMOE_DMA_BODY(N)                                                                                    \
-  dma_body<N, GELU>(Abase, Wbase, Cout, lds0, offA[0], offA[1], offB0, offB1, KT, wm, wn, lane, wave, rows_left, \
-                    crow0, Ndim, n_base)
+  dma_body<N, GELU>(Abase, Wbase, Cout, lds0, offA, offB0, offB1, KT, wm, wn, lane, wave, rows_left, crow0, Ndim, \
+                    n_base)
   // every variant executes the same loads and barriers; a wave row without live subtiles runs the
   // one-subtile variant on clamped rows and stores nothing
   switch (nj) {
