@@ -49,6 +49,10 @@ def lib() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2401_13920_amd.build` "
                            "(or __graft_entry__.build()). There is no fallback path.")
+    # PyTorch ships its own HIP runtime; it has to be resident before this library is mapped, so that both
+    # resolve to one runtime (device pointers and streams come from torch).  Loaded the other way round, the
+    # library binds to the system runtime and every launch on a torch stream fails.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     P, I32, SZ, DBL = C.c_void_p, C.c_int32, C.c_size_t, C.c_double
     D = C.POINTER(locmoe_desc)
