@@ -283,6 +283,28 @@ def test_tuned_gemm_tiles_with_ragged_segments(env):
     run_full(env, wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4, dtype="bf16"), 300)
 
 
+def test_whole_path_bitwise_repeatable(env):
+    """No atomics whose order could matter anywhere on the path: y is bit-identical from run to run, for the
+    row-major and the packed-weight kernels."""
+    torch, lm, hz = env
+    c = wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4)
+    x, home = wl.hidden_states(c)
+    desc = lm.make_desc(c.T, c.d, c.E, c.N, c.h, 300, c.dtype)
+    ws = [wl.expert_weights(c, e) for e in range(c.E)]
+    W_in = torch.stack([hz.to_device(w[0], "bf16") for w in ws]); W_out = torch.stack([hz.to_device(w[1], "bf16") for w in ws])
+    x_dev = hz.to_device(x, c.dtype); home_dev = i32(torch, home)
+    for d_, wi, wo in ((desc, W_in, W_out), (packed_desc(lm, desc),) + pack(env, desc, W_in, W_out)):
+        b = lm.alloc_buffers(d_)
+        ref = None
+        for _ in range(5):
+            b.y.zero_(); b.H.zero_(); b.out.zero_()
+            lm.forward(d_, x_dev, home_dev, None, wi, wo, b)
+            torch.cuda.synchronize()
+            cur = b.y.view(torch.int16).cpu().numpy().tobytes()
+            ref = ref or cur
+            assert cur == ref
+
+
 def test_route_dispatch_deterministic(env):
     torch, lm, hz = env
     c = wl.CONFIGS[2]
