@@ -5,17 +5,21 @@
 // contract over the contiguous axis of both operands ("NT" form): every MFMA fragment is one
 // 16-byte LDS read.  bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// Three kernels share the operand orientation and the epilogue:
-//   ffn_gemm_generic  any shape the descriptor allows, fp32 or bf16 activations (fallback)
-//   ffn_gemm_256      256x256x64 tiles, register-staged double buffer, row-major weights
-//   ffn_gemm_dma      256x256x32 tiles, five LDS stages filled by direct-to-LDS loads, weights
-//                     pre-packed by locmoe_pack_weights into the LDS image of each stage
+// Kernels that share the operand orientation and the epilogue:
+//   ffn_gemm_generic         any shape the descriptor allows, fp32 or bf16 activations (fallback)
+//   ffn_gemm_256             256x256x64 tiles, register-staged double buffer, row-major weights
+//   ffn_gemm_dma_persistent  256x256x32 tiles, LDS rings filled by direct-to-LDS loads, weights pre-packed
+//                            by locmoe_pack_weights into the LDS image of each k-step; one work-group per
+//                            compute unit works through a queue of tiles (expert counts that are multiples
+//                            of 8, up to 512)
+//   ffn_gemm_dma             the same pipeline with one tile per work-group (other expert counts)
 //
 // The weight rows feed the MFMA's A operand and the activation rows its B operand, i.e. the
 // tile is computed transposed (D[n][m]); a lane then owns 4 consecutive output columns n of one
 // row m per accumulator quad and stores them as one 8-byte (bf16) or 16-byte (fp32) vector.
 #include <math.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -297,21 +301,98 @@ __device__ __forceinline__ f32x4 mfma16_bf16(const bf16x8& a, const bf16x8& b, c
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole 32-wide k-step of a 16x16 output
-// tile, and lane l always reads LDS chunk l/16 of its rows.  Measured on this part with random bf16
-// operands, this shape sustains about 1.97 PFLOP/s against 1.47 PFLOP/s for the 32x32x16 shape (clock
+// What the pipeline needs to know about one 256x256 output tile.
+struct DmaTile {
+  const char* Abase;   // first activation row of the tile
+  const char* Wbase;   // first packed block of the tile's 256 weight rows (output columns)
+  uint32_t offA[4];    // per-lane source offsets of this wave's four 1 KiB activation copies
+  int rows_left;       // live rows from the tile's first row to the segment's end (>= 1)
+  size_t crow0;        // first output row
+  int n_base;          // first output column
+};
+// Ring positions, carried from tile to tile: weight slot of the current k-step and the slot that the
+// k-step three ahead goes to; activation slot of the current double step and the slot two ahead.
+struct DmaRing { int wcur, wfill, acur, afill; };
+
+__device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
+                                             int nt, int e, int Kdim, int Ndim, int wave, int lane) {
+  DmaTile t;
+  const int m0 = mt * kBM;
+  t.rows_left = rows - m0;
+  t.Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
+  t.Wbase = (const char*)(Wp + ((size_t)e * Ndim + (size_t)nt * kBN) * (size_t)Kdim);
+  // lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS chunk l%8 receives source chunk
+  // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = 8 * (wave + 8 * j) + (lane >> 3);
+    const int kc = (lane & 7) ^ ((row >> 1) & 7);
+    t.offA[j] = (uint32_t)min(row, t.rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
+  }
+  t.crow0 = (size_t)seg0 + m0;
+  t.n_base = nt * kBN;
+  return t;
+}
+// Stand-in for "the tile after the last": prefetches past the end of `t` re-read its own last blocks
+// (three weight steps, two activation double steps), which nobody consumes.
+__device__ __forceinline__ DmaTile tail_alias(const DmaTile& t, int KT) {
+  DmaTile a = t;
+  a.Wbase = t.Wbase + (size_t)(KT - 3) * kPackBlock;
+  a.Abase = t.Abase + (size_t)((KT >> 1) - 2) * (kDmaBK * 4);
+  return a;
+}
+
+// weights of k-step t of `tile` into ring slot `slot`; this wave copies blocks {wave, wave+8} of 16
+__device__ __forceinline__ void issue_w(const char* wbase, int t, int slot, uint32_t lds0, int wave, int lane) {
+  const char* wb = wbase + (size_t)t * kPackBlock;
+  const uint32_t st = lds0 + kWRing + (uint32_t)slot * kWSlotBytes;
+  const uint32_t off = (uint32_t)(wave * 1024 + lane * 16);
+  dma_1k(wb, off, st + wave * 1024);
+  dma_1k(wb, off + 8 * 1024, st + (wave + 8) * 1024);
+}
+// activations of double step D into ring slot `slot`; this wave copies blocks {wave, wave+8, +16, +24} of 32,
+// a block being 8 rows x 128 B
+__device__ __forceinline__ void issue_a(const char* abase, const uint32_t (&offA)[4], int D, int slot, uint32_t lds0,
+                                        int wave) {
+  const char* ab = abase + (size_t)D * (kDmaBK * 4);
+  const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dma_1k(ab, offA[j], st + (wave + 8 * j) * 1024);
+}
+
+// Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1) W(2), all landed and visible
+// to every wave on return.  Later tiles find the same state because the tile before them prefetched it.
+__device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
+  ring = DmaRing{0, 3, 0, 2};
+  issue_a(t.Abase, t.offA, 0, 0, lds0, wave);
+  issue_w(t.Wbase, 0, 0, lds0, wave, lane);
+  issue_w(t.Wbase, 1, 1, lds0, wave, lane);
+  issue_a(t.Abase, t.offA, 1, 1, lds0, wave);
+  issue_w(t.Wbase, 2, 2, lds0, wave, lane);
+  wait_vmcnt<0>();
+  __syncthreads();
+}
+
+// One output tile.  The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole 32-wide k-step of a
+// 16x16 output tile, and lane l always reads LDS chunk l/16 of its rows.  Measured on this part with random
+// bf16 operands, this shape sustains about 1.97 PFLOP/s against 1.47 PFLOP/s for the 32x32x16 shape (clock
 // management); LDS bytes per flop are identical for the two shapes at this wave tile.
-template <int NJ, bool GELU>
-__device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const char* __restrict__ Wbase,
-                                         uint16_t* __restrict__ Cout, uint32_t lds0, const uint32_t (&offA)[4],
-                                         uint32_t offB0, uint32_t offB1, int KT, int wm, int wn, int lane, int wave,
-                                         int rows_left, size_t crow0, int ldc, int n_base) {
-  // NJ = live 16-row activation tiles of this wave
-  constexpr int NLO = NJ < 4 ? NJ : 4;        // first group of tiles
+//
+// On entry the first three weight steps and two activation double steps of `cur` are in the rings (landed and
+// published); the loop's prefetches run on into `nxt`, so on exit the same holds for `nxt` except that its
+// last prefetches (W(1), W(2), A(1)) and this tile's stores may still be in flight: the caller drains them
+// with vmcnt(0) before the next tile (stores and direct-to-LDS loads do not retire in order relative to
+// each other, so no smaller count is safe there).
+template <int NJ, bool GELU, class F>
+__device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
+                                         uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
+                                         int lane, int wave, int ldc, F&& before_epilogue) {
+  // NJ = live 16-row activation subtiles of this wave
+  constexpr int NLO = NJ < 4 ? NJ : 4;        // first group of subtiles
   constexpr int NHI = NJ - NLO;               // second group (0 for short tiles)
   const int kq = lane >> 4, l16 = lane & 15;
   lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
-  // tile j of this wave: rows (2 j + wm)*16 .. +16 of the work-group tile (interleaved over the two wave rows);
+  // subtile j of this wave: rows (2 j + wm)*16 .. +16 of the work-group tile (interleaved over the two wave rows);
   // a_addr[half][j]: byte offset inside an activation slot for the even / odd k-step of a double step
   int a_addr[2][8], b_addr[4];
 #pragma unroll
@@ -331,23 +412,7 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[ni][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int KD = KT >> 1;  // double steps (KT is even)
-  // weights of k-step t (clamped to the last: tail prefetches are redundant, never consumed) into slot `slot`;
-  // this wave copies blocks {wave, wave+8} of 16
-  auto issue_w = [&](int t, int slot) {
-    const char* wb = Wbase + (size_t)min(t, KT - 1) * kPackBlock;
-    const uint32_t st = lds0 + kWRing + (uint32_t)slot * kWSlotBytes;
-    dma_1k(wb, offB0, st + wave * 1024);
-    dma_1k(wb, offB1, st + (wave + 8) * 1024);
-  };
-  // activations of double step D (clamped) into slot `slot`; this wave copies blocks {wave, wave+8, +16, +24}
-  // of 32, a block being 8 rows x 128 B
-  auto issue_a = [&](int D, int slot) {
-    const char* ab = Abase + (size_t)min(D, KD - 1) * (kDmaBK * 4);
-    const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dma_1k(ab, offA[j], st + (wave + 8 * j) * 1024);
-  };
+  const int KD = KT >> 1;  // double steps (KT is a multiple of 8)
   bf16x8 fw[2][4], fa_lo[4], fa_hi[4];
   auto load_w = [&](auto buf, int wslot) {
     constexpr int B = decltype(buf)::value;
@@ -369,14 +434,16 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
-  int wcur = 0, wfill = 3;  // weight slot of k-step kt; slot that k-step kt+3 goes to
-  int acur = 0, afill = 2;  // activation slot of double step kt/2; slot that double step kt/2+2 goes to
+  // (wave-uniform by construction; said explicitly so that the ring arithmetic stays on the scalar unit)
+  int wcur = __builtin_amdgcn_readfirstlane(ring.wcur), wfill = __builtin_amdgcn_readfirstlane(ring.wfill);
+  int acur = __builtin_amdgcn_readfirstlane(ring.acur), afill = __builtin_amdgcn_readfirstlane(ring.afill);
 
   // One k-step; PAR = kt % 2.  On entry fw[PAR] and fa_lo hold the fragments of step kt; on exit fw[1-PAR] and
   // fa_lo hold those of step kt+1.  The scheduling barriers keep every fragment read ahead of the MFMAs that
   // run while it is in flight.
-  auto step = [&](auto par_, auto npar_, int kt) {
+  auto step = [&](auto par_, auto npar_, auto tail_, int kt) {
     constexpr int PAR = decltype(par_)::value;
+    constexpr bool TAIL = decltype(tail_)::value;  // one of the tile's last four steps: prefetches may run over
     const int wnxt = wcur + 1 == kWSlots ? 0 : wcur + 1;
     const int anxt = PAR == 0 ? acur : (acur + 1 == kASlots ? 0 : acur + 1);  // slot of step kt+1's activations
     load_hi(par_, acur);
@@ -388,9 +455,16 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<6>();   // weights of kt+1 (and, for odd kt, activations of double step (kt+1)/2) have landed
     __syncthreads();   // ... for everybody; nobody reads weight slot kt-1 or, for even kt, activation slot kt/2-1
-    issue_w(kt + 3, wfill);
-    if (PAR == 0) issue_a((kt >> 1) + 2, afill);
-    load_w(npar_, wnxt);       // (for kt+1 == KT: clamped copies of the last step, unused)
+    if (TAIL) {  // past this tile's end the stream runs on into the next tile
+      const int t = kt + 3;
+      const bool over = t >= KT;
+      issue_w(over ? nxt.Wbase : cur.Wbase, over ? t - KT : t, wfill, lds0, wave, lane);
+      if (PAR == 0) issue_a(nxt.Abase, nxt.offA, (kt >> 1) + 2 - KD, afill, lds0, wave);  // kt = KT-4, KT-2
+    } else {
+      issue_w(cur.Wbase, kt + 3, wfill, lds0, wave, lane);
+      if (PAR == 0) issue_a(cur.Abase, cur.offA, (kt >> 1) + 2, afill, lds0, wave);
+    }
+    load_w(npar_, wnxt);       // (for kt+1 == KT: the next tile's first step, read again at its start)
     load_lo(npar_, anxt);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -404,118 +478,199 @@ __device__ __forceinline__ void dma_body(const char* __restrict__ Abase, const c
     acur = anxt;
   };
 
-  // prologue, in the steady state's issue order: A(0) W(0) W(1) A(1) W(2)
-  issue_a(0, 0);
-  issue_w(0, 0);
-  issue_w(1, 1);
-  issue_a(1, 1);
-  issue_w(2, 2);
-  wait_vmcnt<8>();  // A(0) and W(0) have landed (this wave's share); W(1) A(1) W(2) = 8 loads may be in flight
-  __syncthreads();  // ... and everybody's
-  load_w(I0{}, 0);
-  load_lo(I0{}, 0);
-  for (int kt = 0; kt < KT; kt += 2) {
-    step(I0{}, I1{}, kt);
-    step(I1{}, I0{}, kt + 1);
+  load_w(I0{}, wcur);
+  load_lo(I0{}, acur);
+  for (int kt = 0; kt < KT - 4; kt += 2) {
+    step(I0{}, I1{}, std::false_type{}, kt);
+    step(I1{}, I0{}, std::false_type{}, kt + 1);
   }
-  wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
+  step(I0{}, I1{}, std::true_type{}, KT - 4);
+  step(I1{}, I0{}, std::true_type{}, KT - 3);
+  step(I0{}, I1{}, std::true_type{}, KT - 2);
+  step(I1{}, I0{}, std::true_type{}, KT - 1);
+  ring = DmaRing{wcur, wfill, acur, afill};
+  before_epilogue();  // (the persistent kernel starts its next claim here, to have the answer after the stores)
 
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int m = (2 * j + wm) * 16 + l16;
-    if (m < rows_left) {
+    if (m < cur.rows_left) {
 #pragma unroll
       for (int ni = 0; ni < 4; ++ni) {
-        const int n = n_base + wn * 64 + ni * 16 + kq * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
-        store_quad<GELU, false>(Cout, crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
+        const int n = cur.n_base + wn * 64 + ni * 16 + kq * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
+        store_quad<GELU, false>(Cout, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
       }
     }
   }
 }
 
+// every variant executes the same loads and barriers; a wave row without live subtiles runs the
+// one-subtile variant on clamped rows and stores nothing
+template <bool GELU, class F>
+__device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
+                                             uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
+                                             int lane, int wave, int ldc, F&& before_epilogue) {
+  const int nsub = min(16, (cur.rows_left + 15) >> 4);  // live 16-row subtiles of this tile
+  const int nj = __builtin_amdgcn_readfirstlane((nsub - wm + 1) >> 1);  // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
+#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue)
+  switch (nj) {
+    case 8: LOCMOE_DMA_TILE(8); break;
+    case 7: LOCMOE_DMA_TILE(7); break;
+    case 6: LOCMOE_DMA_TILE(6); break;
+    case 5: LOCMOE_DMA_TILE(5); break;
+    case 4: LOCMOE_DMA_TILE(4); break;
+    case 3: LOCMOE_DMA_TILE(3); break;
+    case 2: LOCMOE_DMA_TILE(2); break;
+    default: LOCMOE_DMA_TILE(1); break;
+  }
+#undef LOCMOE_DMA_TILE
+}
+
+// One tile per work-group, segments in buffer order: the shape of the grid for expert counts that the
+// persistent kernel below does not take.
 template <bool GELU>
 __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __restrict__ A,
                                                             const uint16_t* __restrict__ Wp,
                                                             uint16_t* __restrict__ Cout,
                                                             const int32_t* __restrict__ seg_off,
                                                             const int32_t* __restrict__ buf_expert, int Kdim,
-                                                            int Ndim, int MT, int NT, int E) {
+                                                            int Ndim, int MT, int NT) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // Which tile.  Work-groups with ids congruent mod 8 run on one XCD (one L2); XCD x walks the segments
-  // whose rank in descending order of row count is congruent to x, largest first, all tiles of a segment
-  // together with the m-tiles that share a weight tile adjacent.  Long tiles first means the short tiles
-  // of ragged segments fill the last round instead of leaving compute units idle (7.3 tiles per CU in the
-  // second GEMM of the headline shape).  The order is recomputed by every work-group from seg_off
-  // (E <= 1024 integers, in LDS that the pipeline overwrites afterwards).
-  const int id = blockIdx.x;
-  const int tpe = MT * NT;  // tiles per segment
-  int within, r;
-  if (E % 8 == 0) {
-    const int xcd = id & 7, j = id >> 3;
-    const int want = (j / tpe) * 8 + xcd;  // rank in descending order of rows
-    within = j % tpe;
-    int32_t* s_seg = (int32_t*)smem;       // [E+1] then the pick
-    for (int t = tid; t <= E; t += kDmaThreads) s_seg[t] = seg_off[t];
-    __syncthreads();
-    for (int t = tid; t < E; t += kDmaThreads) {
-      const int mine = s_seg[t + 1] - s_seg[t];
-      int rank = 0;
-      for (int q = 0; q < E; ++q) {
-        const int other = s_seg[q + 1] - s_seg[q];
-        rank += (other > mine || (other == mine && q < t)) ? 1 : 0;
-      }
-      if (rank == want) s_seg[E + 1] = t;
-    }
-    __syncthreads();
-    r = s_seg[E + 1];
-    __syncthreads();  // everybody has read the pick before the first stage overwrites this memory
-  } else {
-    within = id % tpe;
-    r = id / tpe;
-  }
+  const int tpe = MT * NT;
+  const int within = blockIdx.x % tpe, r = blockIdx.x / tpe;
   const int mt = within % MT, nt = within / MT;
   const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
-  const int m0 = mt * kBM;
-  if (m0 >= rows) return;
-  const int e = buf_expert[r];
-  const int wm = wave >> 2, wn = wave & 3;
-  const int rows_left = rows - m0;
-  const char* Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
-  const char* Wbase = (const char*)(Wp + ((size_t)e * Ndim + (size_t)nt * kBN) * (size_t)Kdim);
-  // activations: lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS slot l%8 receives chunk
-  // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
-  uint32_t offA[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 8 * (wave + 8 * j) + (lane >> 3);
-    const int kc = (lane & 7) ^ ((row >> 1) & 7);
-    offA[j] = (uint32_t)min(row, rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
-  }
-  const uint32_t offB0 = (uint32_t)(wave * 1024 + lane * 16), offB1 = offB0 + 8 * 1024;
+  if (mt * kBM >= rows) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const int KT = Kdim / kDmaBK;
-  const int nsub = min(16, (rows_left + 15) >> 4);  // live 16-row subtiles of this tile
-  const int nj = (nsub - wm + 1) >> 1;             // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
-  const size_t crow0 = (size_t)seg0 + m0;
-  const int n_base = nt * kBN;
-#define LOCMOE_DMA_BODY(N)                                                                                    \
-  dma_body<N, GELU>(Abase, Wbase, Cout, lds0, offA, offB0, offB1, KT, wm, wn, lane, wave, rows_left, crow0, Ndim, \
-                    n_base)
-  // every variant executes the same loads and barriers; a wave row without live subtiles runs the
-  // one-subtile variant on clamped rows and stores nothing
-  switch (nj) {
-    case 8: LOCMOE_DMA_BODY(8); break;
-    case 7: LOCMOE_DMA_BODY(7); break;
-    case 6: LOCMOE_DMA_BODY(6); break;
-    case 5: LOCMOE_DMA_BODY(5); break;
-    case 4: LOCMOE_DMA_BODY(4); break;
-    case 3: LOCMOE_DMA_BODY(3); break;
-    case 2: LOCMOE_DMA_BODY(2); break;
-    default: LOCMOE_DMA_BODY(1); break;
+  const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
+  const DmaTile nxt = tail_alias(cur, KT);
+  DmaRing ring;
+  dma_prefill(cur, ring, lds0, wave, lane);
+  dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, wave >> 2, wave & 3, lane, wave, Ndim, [] {});
+  wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
+}
+
+// Tile queues of the persistent kernel, one set per launch slot: words 0..7 are the XCDs' next queue
+// positions, word 8 counts the work-groups that are done with the queues.  All zero between launches: the
+// last work-group to finish puts them back (a launch that dies half way takes the context with it, so
+// nothing stale can be left for a later launch).  Launches take slots round-robin, so launches that overlap
+// on one device (other streams) use different sets as long as fewer than kSchedSlots are in flight.
+constexpr int kSchedSlots = 64;
+__device__ unsigned int g_tile_queue[kSchedSlots][16];
+
+// A work-group is done with the queues (its last claim has returned); the last one of the grid clears them.
+__device__ __forceinline__ void leave_queues(unsigned int* queue, unsigned groups) {
+  __threadfence();
+  if (atomicAdd(&queue[8], 1u) == groups - 1u) {
+#pragma unroll
+    for (int i = 0; i < 9; ++i) atomicExch(&queue[i], 0u);
   }
-#undef LOCMOE_DMA_BODY
+}
+
+// Persistent form: one work-group per compute unit works through a queue of tiles, and the operand
+// stream never drains between tiles: the last k-steps of a tile prefetch the first of the next, whose
+// latency is hidden behind the epilogue.  With one work-group per tile every tile paid the launch of a
+// 512-thread, 160 KiB group, the ordering preamble and a cold pipeline; for segments of at most 256 rows
+// (no second m-tile to share the weight stream with) that was a third of the time.
+//
+// Which tiles.  Work-groups with ids congruent mod 8 run on one XCD (one L2).  XCD x owns the segments
+// whose rank in descending order of row count is congruent to x and queues their tiles largest segment
+// first; only non-empty tiles are enumerated, all tiles of a segment together with the m-tiles that share
+// a weight tile adjacent.  The XCD's gridDim/8 work-groups start on the first gridDim/8 tiles and claim
+// further ones from the queue (one atomic add per tile, issued before the epilogue and consumed after it,
+// one tile ahead of the one being computed),
+// so work-groups that run side by side hold neighbouring tiles (shared weight tile in L2), uneven tiles
+// balance themselves, and the short tiles of ragged segments come last.  Every wave keeps the XCD's
+// segment list in two registers (lane k: segment of local rank k and the inclusive tile count up to it;
+// E/8 <= 64), built once in LDS before the pipeline starts.  The claimed index reaches the other waves
+// through the one weight slot that is free between two tiles.
+template <bool GELU>
+__global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uint16_t* __restrict__ A,
+                                                                       const uint16_t* __restrict__ Wp,
+                                                                       uint16_t* __restrict__ Cout,
+                                                                       const int32_t* __restrict__ seg_off,
+                                                                       const int32_t* __restrict__ buf_expert,
+                                                                       int Kdim, int Ndim, int NT, int E,
+                                                                       unsigned launch_id) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int xcd = blockIdx.x & 7, lb = blockIdx.x >> 3, stride = gridDim.x >> 3;
+  const int nloc = E >> 3;  // segments of this XCD
+  int32_t* s_seg = (int32_t*)smem;   // [E+1]
+  int32_t* s_tab = s_seg + E + 1;    // [E/8]: segment of local rank k
+  for (int t = tid; t <= E; t += kDmaThreads) s_seg[t] = seg_off[t];
+  __syncthreads();
+  for (int t = tid; t < E; t += kDmaThreads) {
+    const int mine = s_seg[t + 1] - s_seg[t];
+    int rank = 0;
+    for (int q = 0; q < E; ++q) {
+      const int other = s_seg[q + 1] - s_seg[q];
+      rank += (other > mine || (other == mine && q < t)) ? 1 : 0;
+    }
+    if ((rank & 7) == xcd) s_tab[rank >> 3] = t;
+  }
+  __syncthreads();
+  int tab_seg = 0, tab_cum = 0;  // lane k < nloc: segment of local rank k, tiles of local ranks 0..k
+  {
+    int ntile = 0;
+    if (lane < nloc) {
+      tab_seg = s_tab[lane];
+      const int rows = s_seg[tab_seg + 1] - s_seg[tab_seg];
+      ntile = ((rows + kBM - 1) / kBM) * NT;
+    }
+    tab_cum = ntile;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(tab_cum, o, 64);
+      if (lane >= o) tab_cum += up;
+    }
+  }
+  const int total = __builtin_amdgcn_readfirstlane(__shfl(tab_cum, 63, 64));  // lanes past nloc carry the total
+  __syncthreads();  // everybody has read the tables before the pipeline overwrites this memory
+  unsigned int* queue = g_tile_queue[launch_id % kSchedSlots];
+  const bool dynamic = stride < total;  // else every tile of this XCD is somebody's first
+  if (lb >= total) {
+    if (tid == 0) leave_queues(queue, gridDim.x);
+    return;
+  }
+
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int KT = Kdim / kDmaBK;
+  auto tile_at = [&](int jl) {
+    const int k = __builtin_popcountll(__ballot(tab_cum <= jl));  // local rank of the segment that holds tile jl
+    const int r = __builtin_amdgcn_readfirstlane(__shfl(tab_seg, k, 64));
+    const int before = k ? __builtin_amdgcn_readfirstlane(__shfl(tab_cum, k - 1, 64)) : 0;
+    const int within = jl - before;
+    const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
+    const int mtc = (rows + kBM - 1) / kBM;
+    return make_tile(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim, wave, lane);
+  };
+  int claimed = 0;
+  if (dynamic && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);  // the tile after the first
+  DmaTile cur = tile_at(lb);
+  DmaRing ring;
+  dma_prefill(cur, ring, lds0, wave, lane);
+  for (;;) {
+    // the claim goes from thread 0 to everybody through the weight slot that step 0 of `cur` refills, after
+    // its barrier
+    volatile int* mailbox = (volatile int*)(smem + kWRing + ring.wfill * kWSlotBytes);
+    if (tid == 0) *mailbox = claimed;
+    __syncthreads();
+    const int jn = dynamic ? stride + __builtin_amdgcn_readfirstlane(*mailbox) : total;
+    const bool more = jn < total;
+    const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KT);
+    dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, wave >> 2, wave & 3, lane, wave, Ndim, [&] {
+      if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
+    });
+    wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
+    if (!more) break;
+    cur = nxt;
+  }
+  if (tid == 0) leave_queues(queue, gridDim.x);
 }
 
 // Weight packing (one-time): block (e, nt, kt) of 16 KiB is the LDS image of W[e][nt*256 .. +256][kt*32 .. +32]:
@@ -535,17 +690,47 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint4* __restri
   Wp[q] = W[src];
 }
 
+// compute units of the current device (the persistent kernel's grid), 256 if the query fails; asked once per device
+inline int cu_count() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
+// names a launch's tile queues; one sequence for every instantiation of the kernel
+inline unsigned next_launch_id() {
+  static std::atomic<unsigned> launches{0};
+  return launches.fetch_add(1u) + 1u;
+}
+
 template <bool GELU>
 int launch_dma(const void* A, const void* Wp, void* C, const int32_t* seg_off, const int32_t* buf_expert, int E,
                int rows_max, int Kdim, int Ndim, hipStream_t st) {
   const int MT = ceil_div(rows_max, kBM), NT = Ndim / kBN;
   const long long total = (long long)E * MT * NT;
   if (total > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
+  if (E % 8 == 0 && E <= 512) {
+    auto kern = ffn_gemm_dma_persistent<GELU>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
+      return LOCMOE_ERR_HIP;
+    // one work-group per compute unit (160 KiB of LDS each), a multiple of 8 so that every XCD gets as many
+    const long long groups = std::min<long long>((cu_count() / 8) * 8, (total + 7) / 8 * 8);
+    const unsigned launch_id = next_launch_id();
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
+                       (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, NT, E, launch_id);
+    return launch_status();
+  }
   auto kern = ffn_gemm_dma<GELU>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
     return LOCMOE_ERR_HIP;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
-                     (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT, E);
+                     (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT);
   return launch_status();
 }
 

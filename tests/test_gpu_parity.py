@@ -281,6 +281,8 @@ def test_tuned_gemm_tiles_with_ragged_segments(env):
     # d, h multiples of the tuned tile; capacity spans several 256-row tiles with ragged tails
     run_full(env, wl.small_config(T=4096, d=256, E=4, N=2, h=512, clusters=3), 700)
     run_full(env, wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4, dtype="bf16"), 300)
+    # many segments for few tiles: empty segments, one- and two-tile segments in one persistent launch
+    run_full(env, wl.small_config(T=6000, d=256, E=64, N=8, h=512, clusters=5), 300)
 
 
 def test_whole_path_bitwise_repeatable(env):
@@ -303,6 +305,43 @@ def test_whole_path_bitwise_repeatable(env):
             cur = b.y.view(torch.int16).cpu().numpy().tobytes()
             ref = ref or cur
             assert cur == ref
+
+
+def test_ffn_tile_queues_across_launches_and_streams(env):
+    """The persistent grouped GEMM keeps its tile queues in device memory, one set per launch slot.  More
+    launches in a row than there are slots, and launches that overlap on two streams, must give the bits of
+    a single launch (which is checked against the oracle first)."""
+    torch, lm, hz = env
+    # 8 experts = one segment per XCD, up to 2 x 32 tiles each for 32 work-groups: tiles are claimed dynamically
+    c = wl.small_config(T=3000, d=512, E=8, N=2, h=8192, clusters=4)
+    run_full(env, c, 300)
+    x, home = wl.hidden_states(c)
+    desc = lm.make_desc(c.T, c.d, c.E, c.N, c.h, 300, c.dtype)
+    ws = [wl.expert_weights(c, e) for e in range(c.E)]
+    W_in = torch.stack([hz.to_device(w[0], "bf16") for w in ws]); W_out = torch.stack([hz.to_device(w[1], "bf16") for w in ws])
+    dp = packed_desc(lm, desc)
+    Wi, Wo = pack(env, desc, W_in, W_out)
+    b = lm.alloc_buffers(dp)
+    lm.forward(dp, hz.to_device(x, c.dtype), i32(torch, home), None, Wi, Wo, b)
+    torch.cuda.synchronize()
+    K = int(b.seg_off[-1])
+    ref = b.out[:K].view(torch.int16).cpu().numpy().tobytes()
+    for it in range(70):                                   # more launches than queue slots
+        b.H.zero_(); b.out.zero_()
+        lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out)
+        torch.cuda.synchronize()
+        assert b.out[:K].view(torch.int16).cpu().numpy().tobytes() == ref, it
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]   # default priority
+    Hs = [torch.zeros_like(b.H) for _ in streams]; outs = [torch.zeros_like(b.out) for _ in streams]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for st, H, out in zip(streams, Hs, outs):
+            lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, H, out, stream=st)
+        torch.cuda.synchronize()
+        for out in outs:
+            assert out[:K].view(torch.int16).cpu().numpy().tobytes() == ref, rep
+            out.zero_()
+        torch.cuda.synchronize()
 
 
 def test_route_dispatch_deterministic(env):
