@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the two grouped-GEMM kernels at the bench workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (KiB per dispatch; profiles/bench_config4_kernels_and_hbm_counters.txt).  FETCH_SIZE is scaled by 2.0,
 # the factor the same counter needs for a plain 1 GiB copy in the same run; WRITE_SIZE needs none.
-PMC_KIB = {"ffn_in": (5635119.5, 814890.9), "ffn_out": (5872954.3, 203602.4)}
+PMC_KIB = {"ffn_in": (6532064.5, 849942.9), "ffn_out": (6125987.5, 220929.5)}
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
@@ -182,7 +182,7 @@ def main() -> int:
                            "mfma_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
     dom = "ffn_in" if ms["ffn_in"] >= ms["ffn_out"] else "ffn_out"
     achieved = flops / (ms[dom] * 1e-3) / 1e12
-    kname = "ffn_gemm_dma" if desc.w_packed else "ffn_gemm_256"
+    kname = "ffn_gemm_dma_persistent" if desc.w_packed else "ffn_gemm_256"
     roofline = {"bound": "mfma", "kernel": f"{kname} ({dom})", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": (round((PMC_KIB[dom][0] * FETCH_FACTOR + PMC_KIB[dom][1] * WRITE_FACTOR) * 1024)
