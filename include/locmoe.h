@@ -138,7 +138,11 @@ int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* 
  * columns 8*c .. 8*c+7 of the step with c = (p%4) ^ ((r/2)%4) - the LDS image the kernel consumes.
  * With desc->w_packed = 1 the three expert_ffn entry points take the packed tensors in place of
  * W_in / W_out (LOCMOE_ERR_ARG if the shape or dtype cannot use them); results are the same
- * to rounding order.  W_in [E,h,d], W_out [E,d,h] device bf16 (read); packed tensors device (written). */
+ * to rounding order.  W_in [E,h,d], W_out [E,d,h] device bf16 (read); packed tensors device (written).
+ * State: the packed-weight kernels (E a multiple of 8, at most 512) hand out tiles through queue words
+ * in a small device array that the library owns (no allocation; 64 sets, taken round-robin per launch
+ * and cleared by the launch itself).  Launches may overlap on other streams or host threads as long as
+ * fewer than 64 of them are in flight on one device.  Every other entry point is stateless. */
 size_t locmoe_packed_weights_bytes(const locmoe_desc* desc);
 int locmoe_pack_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_packed,
                         void* W_out_packed, void* stream);
