@@ -275,7 +275,14 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 // ...), so a ragged tile skips MFMAs evenly across waves, at 32-row granularity overall.
 // ---------------------------------------------------------------------------------------------
 constexpr int kDmaBK = 32;
-constexpr int kDmaThreads = 512;
+// Waves per work-group of the direct-to-LDS kernels.  The second GEMM runs the four-wave form (a third less
+// LDS read traffic: measured +5 %); the first keeps eight waves, because its GeLU epilogue is vector work
+// that one wave per SIMD cannot overlap with anything (measured -1 % with four).
+#ifdef LOCMOE_FFN_WAVES
+template <bool GELU> constexpr int kDmaWaves = LOCMOE_FFN_WAVES;
+#else
+template <bool GELU> constexpr int kDmaWaves = GELU ? 8 : 4;
+#endif
 constexpr int kWSlots = 4, kWSlotBytes = kBN * kDmaBK * 2;     // 4 x 16 KiB
 constexpr int kASlots = 3, kASlotBytes = kBM * kDmaBK * 2 * 2;  // 3 x 32 KiB
 constexpr int kWRing = kASlots * kASlotBytes;                   // weights ring starts after the activations ring
@@ -301,11 +308,29 @@ __device__ __forceinline__ f32x4 mfma16_bf16(const bf16x8& a, const bf16x8& b, c
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// What the pipeline needs to know about one 256x256 output tile.
+// The same MFMA with the accumulator pinned to accumulation registers and updated in place.  With all 256
+// of them holding accumulators the compiler's own register assignment routes most MFMAs through a spare
+// tuple (four copies per MFMA); written this way there are none.  The compiler does not see an MFMA here,
+// so it inserts none of the wait states an MFMA needs around other instructions; the two places that need
+// them are handled by hand: the results are read only after explicit wait states behind the K loop, and
+// the accumulators are never zeroed by register writes (an MFMA that follows such a write too closely
+// reads the old value: seen as wrong last components of some accumulators) but started by the first
+// k-step with the constant 0 as its addend.
+template <bool FIRST>
+__device__ __forceinline__ void mfma16_acc(f32x4& c, const bf16x8& a, const bf16x8& b) {
+  if (FIRST)  // the tile's first k-step starts from the constant 0: no zeroing writes that an MFMA could read too early
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(c) : "v"(a), "v"(b));
+  else
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+// What the pipeline needs to know about one 256x256 output tile; W = waves of the work-group (8 or 4).
+template <int W>
 struct DmaTile {
+  static constexpr int NA = 32 / W;  // 1 KiB activation copies per wave and double step
   const char* Abase;   // first activation row of the tile
   const char* Wbase;   // first packed block of the tile's 256 weight rows (output columns)
-  uint32_t offA[4];    // per-lane source offsets of this wave's four 1 KiB activation copies
+  uint32_t offA[NA];   // per-lane source offsets of this wave's activation copies
   int rows_left;       // live rows from the tile's first row to the segment's end (>= 1)
   size_t crow0;        // first output row
   int n_base;          // first output column
@@ -314,9 +339,10 @@ struct DmaTile {
 // k-step three ahead goes to; activation slot of the current double step and the slot two ahead.
 struct DmaRing { int wcur, wfill, acur, afill; };
 
-__device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
-                                             int nt, int e, int Kdim, int Ndim, int wave, int lane) {
-  DmaTile t;
+template <int W>
+__device__ __forceinline__ DmaTile<W> make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
+                                                int nt, int e, int Kdim, int Ndim, int wave, int lane) {
+  DmaTile<W> t;
   const int m0 = mt * kBM;
   t.rows_left = rows - m0;
   t.Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
@@ -324,8 +350,8 @@ __device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* 
   // lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS chunk l%8 receives source chunk
   // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 8 * (wave + 8 * j) + (lane >> 3);
+  for (int j = 0; j < DmaTile<W>::NA; ++j) {
+    const int row = 8 * (wave + W * j) + (lane >> 3);
     const int kc = (lane & 7) ^ ((row >> 1) & 7);
     t.offA[j] = (uint32_t)min(row, t.rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
   }
@@ -335,40 +361,52 @@ __device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* 
 }
 // Stand-in for "the tile after the last": prefetches past the end of `t` re-read its own last blocks
 // (three weight steps, two activation double steps), which nobody consumes.
-__device__ __forceinline__ DmaTile tail_alias(const DmaTile& t, int KT) {
-  DmaTile a = t;
+template <int W>
+__device__ __forceinline__ DmaTile<W> tail_alias(const DmaTile<W>& t, int KT) {
+  DmaTile<W> a = t;
   a.Wbase = t.Wbase + (size_t)(KT - 3) * kPackBlock;
   a.Abase = t.Abase + (size_t)((KT >> 1) - 2) * (kDmaBK * 4);
   return a;
 }
 
-// weights of k-step t of `tile` into ring slot `slot`; this wave copies blocks {wave, wave+8} of 16
-__device__ __forceinline__ void issue_w(const char* wbase, int t, int slot, uint32_t lds0, int wave, int lane) {
+// copy i of this wave's 16/W copies of the weights of k-step t into ring slot `slot` (1 KiB blocks wave + W i)
+template <int W>
+__device__ __forceinline__ void issue_w1(const char* wbase, int t, int slot, int i, uint32_t lds0, int wave,
+                                         int lane) {
   const char* wb = wbase + (size_t)t * kPackBlock;
   const uint32_t st = lds0 + kWRing + (uint32_t)slot * kWSlotBytes;
-  const uint32_t off = (uint32_t)(wave * 1024 + lane * 16);
-  dma_1k(wb, off, st + wave * 1024);
-  dma_1k(wb, off + 8 * 1024, st + (wave + 8) * 1024);
+  const uint32_t blk = (uint32_t)(wave + W * i) * 1024;
+  dma_1k(wb, blk + lane * 16, st + blk);
 }
-// activations of double step D into ring slot `slot`; this wave copies blocks {wave, wave+8, +16, +24} of 32,
-// a block being 8 rows x 128 B
-__device__ __forceinline__ void issue_a(const char* abase, const uint32_t (&offA)[4], int D, int slot, uint32_t lds0,
-                                        int wave) {
-  const char* ab = abase + (size_t)D * (kDmaBK * 4);
-  const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
+template <int W>
+__device__ __forceinline__ void issue_w(const char* wbase, int t, int slot, uint32_t lds0, int wave, int lane) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) dma_1k(ab, offA[j], st + (wave + 8 * j) * 1024);
+  for (int i = 0; i < 16 / W; ++i) issue_w1<W>(wbase, t, slot, i, lds0, wave, lane);
+}
+// copy j of this wave's 32/W copies of the activations of double step D into ring slot `slot` (blocks
+// wave + W j of 32, a block being 8 rows x 128 B)
+template <int W>
+__device__ __forceinline__ void issue_a1(const DmaTile<W>& t, int D, int slot, int j, uint32_t lds0, int wave) {
+  const char* ab = t.Abase + (size_t)D * (kDmaBK * 4);
+  const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
+  dma_1k(ab, t.offA[j], st + (wave + W * j) * 1024);
+}
+template <int W>
+__device__ __forceinline__ void issue_a(const DmaTile<W>& t, int D, int slot, uint32_t lds0, int wave) {
+#pragma unroll
+  for (int j = 0; j < DmaTile<W>::NA; ++j) issue_a1<W>(t, D, slot, j, lds0, wave);
 }
 
 // Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1) W(2), all landed and visible
 // to every wave on return.  Later tiles find the same state because the tile before them prefetched it.
-__device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
+template <int W>
+__device__ __forceinline__ void dma_prefill(const DmaTile<W>& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
   ring = DmaRing{0, 3, 0, 2};
-  issue_a(t.Abase, t.offA, 0, 0, lds0, wave);
-  issue_w(t.Wbase, 0, 0, lds0, wave, lane);
-  issue_w(t.Wbase, 1, 1, lds0, wave, lane);
-  issue_a(t.Abase, t.offA, 1, 1, lds0, wave);
-  issue_w(t.Wbase, 2, 2, lds0, wave, lane);
+  issue_a<W>(t, 0, 0, lds0, wave);
+  issue_w<W>(t.Wbase, 0, 0, lds0, wave, lane);
+  issue_w<W>(t.Wbase, 1, 1, lds0, wave, lane);
+  issue_a<W>(t, 1, 1, lds0, wave);
+  issue_w<W>(t.Wbase, 2, 2, lds0, wave, lane);
   wait_vmcnt<0>();
   __syncthreads();
 }
@@ -384,7 +422,7 @@ __device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uin
 // with vmcnt(0) before the next tile (stores and direct-to-LDS loads do not retire in order relative to
 // each other, so no smaller count is safe there).
 template <int NJ, bool GELU, class F>
-__device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
+__device__ __forceinline__ void dma_tile(const DmaTile<8>& cur, const DmaTile<8>& nxt, DmaRing& ring,
                                          uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
                                          int lane, int wave, int ldc, F&& before_epilogue) {
   // NJ = live 16-row activation subtiles of this wave
@@ -458,11 +496,11 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
     if (TAIL) {  // past this tile's end the stream runs on into the next tile
       const int t = kt + 3;
       const bool over = t >= KT;
-      issue_w(over ? nxt.Wbase : cur.Wbase, over ? t - KT : t, wfill, lds0, wave, lane);
-      if (PAR == 0) issue_a(nxt.Abase, nxt.offA, (kt >> 1) + 2 - KD, afill, lds0, wave);  // kt = KT-4, KT-2
+      issue_w<8>(over ? nxt.Wbase : cur.Wbase, over ? t - KT : t, wfill, lds0, wave, lane);
+      if (PAR == 0) issue_a<8>(nxt, (kt >> 1) + 2 - KD, afill, lds0, wave);  // kt = KT-4, KT-2
     } else {
-      issue_w(cur.Wbase, kt + 3, wfill, lds0, wave, lane);
-      if (PAR == 0) issue_a(cur.Abase, cur.offA, (kt >> 1) + 2, afill, lds0, wave);
+      issue_w<8>(cur.Wbase, kt + 3, wfill, lds0, wave, lane);
+      if (PAR == 0) issue_a<8>(cur, (kt >> 1) + 2, afill, lds0, wave);
     }
     load_w(npar_, wnxt);       // (for kt+1 == KT: the next tile's first step, read again at its start)
     load_lo(npar_, anxt);
@@ -504,15 +542,129 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
   }
 }
 
+// The same tile with four waves, one per SIMD (2 along m x 2 along n, 128x128 per wave, 256 accumulator
+// registers): a third less LDS read traffic per flop than the eight-wave form (16 fragment reads feed 64
+// MFMAs instead of 12 feeding 32).  With a single wave per SIMD nothing else hides the issue slots of the
+// fragment reads and direct-to-LDS copies, so they are interleaved one by one between the MFMAs.
+// Per wave and k-step: 4 weight copies, and 8 activation copies when the step is even; at the barrier of
+// step kt everything issued after the weights of kt+1 is 12 copies (either parity), hence vmcnt(12).
+template <int NJ, bool GELU, class F>
+__device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4>& nxt, DmaRing& ring,
+                                          uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
+                                          int lane, int wave, int ldc, F&& before_epilogue) {
+  constexpr int NLO = NJ < 4 ? NJ : 4;
+  constexpr int NHI = NJ - NLO;
+  const int kq = lane >> 4, l16 = lane & 15;
+  lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
+  // subtile j of this wave: rows (2 j + wm)*16 .. +16; weight subtile ni: rows wn*128 + ni*16 .. +16.  The
+  // swizzle terms do not depend on j or ni, so the per-subtile addresses are constant offsets from these.
+  const int ra = wm * 16 + l16, rb = wn * 128 + l16;
+  const int a_base0 = ra * 128 + ((kq ^ ((ra >> 1) & 7)) << 4);
+  const int a_base1 = ra * 128 + (((4 + kq) ^ ((ra >> 1) & 7)) << 4);
+  const int b_base = kWRing + rb * 64 + ((kq ^ ((rb >> 1) & 3)) << 4);
+  f32x4 acc[8][8];  // written, not accumulated into, by the first k-step
+
+  const int KD = KT >> 1;
+  bf16x8 fw[2][8], fa_lo[4], fa_hi[4];
+  auto read_w = [&](int ni, int wslot) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)wslot * kWSlotBytes + b_base + ni * 1024);
+  };
+  auto read_a = [&](int half, int j, int aslot) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)aslot * kASlotBytes +
+                                                                (half ? a_base1 : a_base0) + j * 4096);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  int wcur = __builtin_amdgcn_readfirstlane(ring.wcur), wfill = __builtin_amdgcn_readfirstlane(ring.wfill);
+  int acur = __builtin_amdgcn_readfirstlane(ring.acur), afill = __builtin_amdgcn_readfirstlane(ring.afill);
+
+  auto step = [&](auto par_, auto tail_, auto first_, int kt) {
+    constexpr int PAR = decltype(par_)::value;
+    constexpr bool FIRST = decltype(first_)::value;
+    constexpr int NPAR = 1 - PAR;
+    constexpr bool TAIL = decltype(tail_)::value;
+    const int wnxt = wcur + 1 == kWSlots ? 0 : wcur + 1;
+    const int anxt = PAR == 0 ? acur : (acur + 1 == kASlots ? 0 : acur + 1);
+    // first group of subtiles; the second group's activation fragments are read in between
+#pragma unroll
+    for (int j = 0; j < NLO; ++j) {
+      if (j < NHI) fa_hi[j] = read_a(PAR, 4 + j, acur);
+#pragma unroll
+      for (int ni = 0; ni < 8; ++ni) mfma16_acc<FIRST>(acc[ni][j], fw[PAR][ni], fa_lo[j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt<12>();  // weights of kt+1 (and, for odd kt, activations of double step (kt+1)/2) have landed
+    __syncthreads();   // ... for everybody; nobody reads weight slot kt-1 or, for even kt, activation slot kt/2-1
+    // second group of subtiles, with the other work spread between its MFMAs: the next step's fragment
+    // reads first (needed soonest), then the copies of step kt+3 and, on even steps, double step kt/2+2
+    constexpr int NREAD = 8 + NLO, NCOPY = 4 + (PAR == 0 ? 8 : 0), NITEM = NREAD + NCOPY, NM = NHI * 8;
+    const int tw = kt + 3;
+    const bool w_over = TAIL && tw >= KT;
+    const char* wsrc = w_over ? nxt.Wbase : cur.Wbase;
+    const int wt = w_over ? tw - KT : tw;
+    const int aD = TAIL ? (kt >> 1) + 2 - KD : (kt >> 1) + 2;  // (even steps; the tail's two land in nxt)
+#pragma unroll
+    for (int i = 0; i < NITEM; ++i) {
+      if (i < 8) fw[NPAR][i] = read_w(i, wnxt);
+      else if (i < NREAD) fa_lo[i - 8] = read_a(NPAR, i - 8, anxt);
+      else if (i < NREAD + 4) issue_w1<4>(wsrc, wt, wfill, i - NREAD, lds0, wave, lane);
+      else issue_a1<4>(TAIL ? nxt : cur, aD, afill, i - NREAD - 4, lds0, wave);
+#pragma unroll
+      for (int q = i * NM / NITEM; q < (i + 1) * NM / NITEM; ++q)
+        mfma16_acc<FIRST>(acc[q & 7][4 + (q >> 3)], fw[PAR][q & 7], fa_hi[q >> 3]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wcur = wnxt;
+    wfill = wfill + 1 == kWSlots ? 0 : wfill + 1;
+    if (PAR == 0) afill = afill + 1 == kASlots ? 0 : afill + 1;
+    acur = anxt;
+  };
+
+#pragma unroll
+  for (int ni = 0; ni < 8; ++ni) fw[0][ni] = read_w(ni, wcur);
+#pragma unroll
+  for (int j = 0; j < NLO; ++j) fa_lo[j] = read_a(0, j, acur);
+  step(I0{}, std::false_type{}, std::true_type{}, 0);
+  step(I1{}, std::false_type{}, std::false_type{}, 1);
+  for (int kt = 2; kt < KT - 4; kt += 2) {
+    step(I0{}, std::false_type{}, std::false_type{}, kt);
+    step(I1{}, std::false_type{}, std::false_type{}, kt + 1);
+  }
+  step(I0{}, std::true_type{}, std::false_type{}, KT - 4);
+  step(I1{}, std::true_type{}, std::false_type{}, KT - 3);
+  step(I0{}, std::true_type{}, std::false_type{}, KT - 2);
+  step(I1{}, std::true_type{}, std::false_type{}, KT - 1);
+  ring = DmaRing{wcur, wfill, acur, afill};
+  __builtin_amdgcn_sched_barrier(0);  // (nothing that reads an accumulator may be scheduled above the wait states)
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs have written their accumulators
+  __builtin_amdgcn_sched_barrier(0);
+  before_epilogue();
+
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int m = (2 * j + wm) * 16 + l16;
+    if (m < cur.rows_left) {
+#pragma unroll
+      for (int ni = 0; ni < 8; ++ni) {
+        const int n = cur.n_base + wn * 128 + ni * 16 + kq * 4;
+        store_quad<GELU, false>(Cout, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
+      }
+    }
+  }
+}
+
 // every variant executes the same loads and barriers; a wave row without live subtiles runs the
 // one-subtile variant on clamped rows and stores nothing
-template <bool GELU, class F>
-__device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
-                                             uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
-                                             int lane, int wave, int ldc, F&& before_epilogue) {
+template <bool GELU, int W, class F>
+__device__ __forceinline__ void dma_tile_any(const DmaTile<W>& cur, const DmaTile<W>& nxt, DmaRing& ring,
+                                             uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int lane, int wave,
+                                             int ldc, F&& before_epilogue) {
+  const int wm = W == 8 ? wave >> 2 : wave >> 1, wn = W == 8 ? wave & 3 : wave & 1;
   const int nsub = min(16, (cur.rows_left + 15) >> 4);  // live 16-row subtiles of this tile
   const int nj = __builtin_amdgcn_readfirstlane((nsub - wm + 1) >> 1);  // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
-#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue)
+#define LOCMOE_DMA_TILE(N)                                                                              \
+  if constexpr (W == 8) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue); \
+  else dma_tile4<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue)
   switch (nj) {
     case 8: LOCMOE_DMA_TILE(8); break;
     case 7: LOCMOE_DMA_TILE(7); break;
@@ -528,8 +680,8 @@ __device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& 
 
 // One tile per work-group, segments in buffer order: the shape of the grid for expert counts that the
 // persistent kernel below does not take.
-template <bool GELU>
-__global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __restrict__ A,
+template <bool GELU, int W>
+__global__ __launch_bounds__(W * 64) void ffn_gemm_dma(const uint16_t* __restrict__ A,
                                                             const uint16_t* __restrict__ Wp,
                                                             uint16_t* __restrict__ Cout,
                                                             const int32_t* __restrict__ seg_off,
@@ -545,11 +697,11 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   if (mt * kBM >= rows) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const int KT = Kdim / kDmaBK;
-  const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
-  const DmaTile nxt = tail_alias(cur, KT);
+  const DmaTile<W> cur = make_tile<W>(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
+  const DmaTile<W> nxt = tail_alias<W>(cur, KT);
   DmaRing ring;
-  dma_prefill(cur, ring, lds0, wave, lane);
-  dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, wave >> 2, wave & 3, lane, wave, Ndim, [] {});
+  dma_prefill<W>(cur, ring, lds0, wave, lane);
+  dma_tile_any<GELU, W>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [] {});
   wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
 }
 
@@ -587,8 +739,8 @@ __device__ __forceinline__ void leave_queues(unsigned int* queue, unsigned group
 // segment list in two registers (lane k: segment of local rank k and the inclusive tile count up to it;
 // E/8 <= 64), built once in LDS before the pipeline starts.  The claimed index reaches the other waves
 // through the one weight slot that is free between two tiles.
-template <bool GELU>
-__global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uint16_t* __restrict__ A,
+template <bool GELU, int W>
+__global__ __launch_bounds__(W * 64) void ffn_gemm_dma_persistent(const uint16_t* __restrict__ A,
                                                                        const uint16_t* __restrict__ Wp,
                                                                        uint16_t* __restrict__ Cout,
                                                                        const int32_t* __restrict__ seg_off,
@@ -602,9 +754,9 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
   const int nloc = E >> 3;  // segments of this XCD
   int32_t* s_seg = (int32_t*)smem;   // [E+1]
   int32_t* s_tab = s_seg + E + 1;    // [E/8]: segment of local rank k
-  for (int t = tid; t <= E; t += kDmaThreads) s_seg[t] = seg_off[t];
+  for (int t = tid; t <= E; t += W * 64) s_seg[t] = seg_off[t];
   __syncthreads();
-  for (int t = tid; t < E; t += kDmaThreads) {
+  for (int t = tid; t < E; t += W * 64) {
     const int mine = s_seg[t + 1] - s_seg[t];
     int rank = 0;
     for (int q = 0; q < E; ++q) {
@@ -647,13 +799,13 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     const int within = jl - before;
     const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
     const int mtc = (rows + kBM - 1) / kBM;
-    return make_tile(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim, wave, lane);
+    return make_tile<W>(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim, wave, lane);
   };
   int claimed = 0;
   if (dynamic && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);  // the tile after the first
-  DmaTile cur = tile_at(lb);
+  DmaTile<W> cur = tile_at(lb);
   DmaRing ring;
-  dma_prefill(cur, ring, lds0, wave, lane);
+  dma_prefill<W>(cur, ring, lds0, wave, lane);
   for (;;) {
     // the claim goes from thread 0 to everybody through the weight slot that step 0 of `cur` refills, after
     // its barrier
@@ -662,8 +814,8 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     __syncthreads();
     const int jn = dynamic ? stride + __builtin_amdgcn_readfirstlane(*mailbox) : total;
     const bool more = jn < total;
-    const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KT);
-    dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, wave >> 2, wave & 3, lane, wave, Ndim, [&] {
+    const DmaTile<W> nxt = more ? tile_at(jn) : tail_alias<W>(cur, KT);
+    dma_tile_any<GELU, W>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [&] {
       if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
     });
     wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
@@ -716,20 +868,20 @@ int launch_dma(const void* A, const void* Wp, void* C, const int32_t* seg_off, c
   const long long total = (long long)E * MT * NT;
   if (total > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
   if (E % 8 == 0 && E <= 512) {
-    auto kern = ffn_gemm_dma_persistent<GELU>;
+    auto kern = ffn_gemm_dma_persistent<GELU, kDmaWaves<GELU>>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
       return LOCMOE_ERR_HIP;
     // one work-group per compute unit (160 KiB of LDS each), a multiple of 8 so that every XCD gets as many
     const long long groups = std::min<long long>((cu_count() / 8) * 8, (total + 7) / 8 * 8);
     const unsigned launch_id = next_launch_id();
-    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaWaves<GELU> * 64), kDmaSmem, st, (const uint16_t*)A,
                        (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, NT, E, launch_id);
     return launch_status();
   }
-  auto kern = ffn_gemm_dma<GELU>;
+  auto kern = ffn_gemm_dma<GELU, kDmaWaves<GELU>>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
     return LOCMOE_ERR_HIP;
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaWaves<GELU> * 64), kDmaSmem, st, (const uint16_t*)A,
                      (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT);
   return launch_status();
 }
