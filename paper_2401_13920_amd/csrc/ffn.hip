@@ -9,9 +9,9 @@
 //   ffn_gemm_generic         any shape the descriptor allows, fp32 or bf16 activations (fallback)
 //   ffn_gemm_256             256x256x64 tiles, register-staged double buffer, row-major weights
 //   ffn_gemm_dma_persistent  256x256x32 tiles, LDS rings filled by direct-to-LDS loads, weights pre-packed
-//                            by locmoe_pack_weights into the LDS image of each k-step; one work-group per
-//                            compute unit works through a queue of tiles (expert counts that are multiples
-//                            of 8, up to 512)
+//                            by locmoe_pack_weights into the LDS image of each k-step; four waves with the
+//                            accumulators in the accumulation registers; one work-group per compute unit
+//                            works through a queue of tiles (expert counts that are multiples of 8, up to 512)
 //   ffn_gemm_dma             the same pipeline with one tile per work-group (other expert counts)
 //
 // The weight rows feed the MFMA's A operand and the activation rows its B operand, i.e. the
@@ -275,14 +275,8 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 // ...), so a ragged tile skips MFMAs evenly across waves, at 32-row granularity overall.
 // ---------------------------------------------------------------------------------------------
 constexpr int kDmaBK = 32;
-// Waves per work-group of the direct-to-LDS kernels.  The second GEMM runs the four-wave form (a third less
-// LDS read traffic: measured +5 %); the first keeps eight waves, because its GeLU epilogue is vector work
-// that one wave per SIMD cannot overlap with anything (measured -1 % with four).
-#ifdef LOCMOE_FFN_WAVES
-template <bool GELU> constexpr int kDmaWaves = LOCMOE_FFN_WAVES;
-#else
-template <bool GELU> constexpr int kDmaWaves = GELU ? 8 : 4;
-#endif
+constexpr int kDmaWaves = 4;               // one wave per SIMD
+constexpr int kDmaThreads = kDmaWaves * 64;
 constexpr int kWSlots = 4, kWSlotBytes = kBN * kDmaBK * 2;     // 4 x 16 KiB
 constexpr int kASlots = 3, kASlotBytes = kBM * kDmaBK * 2 * 2;  // 3 x 32 KiB
 constexpr int kWRing = kASlots * kASlotBytes;                   // weights ring starts after the activations ring
@@ -304,30 +298,25 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-__device__ __forceinline__ f32x4 mfma16_bf16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-// The same MFMA with the accumulator pinned to accumulation registers and updated in place.  With all 256
+// v_mfma_f32_16x16x32_bf16 with the accumulator pinned to accumulation registers and updated in place.  With all 256
 // of them holding accumulators the compiler's own register assignment routes most MFMAs through a spare
 // tuple (four copies per MFMA); written this way there are none.  The compiler does not see an MFMA here,
-// so it inserts none of the wait states an MFMA needs around other instructions; the two places that need
-// them are handled by hand: the results are read only after explicit wait states behind the K loop, and
-// the accumulators are never zeroed by register writes (an MFMA that follows such a write too closely
-// reads the old value: seen as wrong last components of some accumulators) but started by the first
-// k-step with the constant 0 as its addend.
-template <bool FIRST>
+// so it inserts none of the wait states an MFMA needs around other instructions; the places that need
+// them are handled by hand: the results are read only after explicit wait states behind the K loop; the
+// accumulators are never zeroed by register writes (an MFMA that follows such a write too closely reads
+// the old value: seen as wrong last components of some accumulators) but by MFMAs of a zero operand, and
+// that operand is pinned behind wait states of its own (without them: NaNs).
+template <bool FROM_ZERO>
 __device__ __forceinline__ void mfma16_acc(f32x4& c, const bf16x8& a, const bf16x8& b) {
-  if (FIRST)  // the tile's first k-step starts from the constant 0: no zeroing writes that an MFMA could read too early
+  if (FROM_ZERO)  // c = a.b + 0
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(c) : "v"(a), "v"(b));
-  else
+  else            // c += a.b
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
-// What the pipeline needs to know about one 256x256 output tile; W = waves of the work-group (8 or 4).
-template <int W>
+// What the pipeline needs to know about one 256x256 output tile.
 struct DmaTile {
-  static constexpr int NA = 32 / W;  // 1 KiB activation copies per wave and double step
+  static constexpr int NA = 32 / kDmaWaves;  // 1 KiB activation copies per wave and double step
   const char* Abase;   // first activation row of the tile
   const char* Wbase;   // first packed block of the tile's 256 weight rows (output columns)
   uint32_t offA[NA];   // per-lane source offsets of this wave's activation copies
@@ -339,10 +328,9 @@ struct DmaTile {
 // k-step three ahead goes to; activation slot of the current double step and the slot two ahead.
 struct DmaRing { int wcur, wfill, acur, afill; };
 
-template <int W>
-__device__ __forceinline__ DmaTile<W> make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
+__device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
                                                 int nt, int e, int Kdim, int Ndim, int wave, int lane) {
-  DmaTile<W> t;
+  DmaTile t;
   const int m0 = mt * kBM;
   t.rows_left = rows - m0;
   t.Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
@@ -350,8 +338,8 @@ __device__ __forceinline__ DmaTile<W> make_tile(const uint16_t* A, const uint16_
   // lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS chunk l%8 receives source chunk
   // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
 #pragma unroll
-  for (int j = 0; j < DmaTile<W>::NA; ++j) {
-    const int row = 8 * (wave + W * j) + (lane >> 3);
+  for (int j = 0; j < DmaTile::NA; ++j) {
+    const int row = 8 * (wave + kDmaWaves * j) + (lane >> 3);
     const int kc = (lane & 7) ^ ((row >> 1) & 7);
     t.offA[j] = (uint32_t)min(row, t.rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
   }
@@ -361,60 +349,61 @@ __device__ __forceinline__ DmaTile<W> make_tile(const uint16_t* A, const uint16_
 }
 // Stand-in for "the tile after the last": prefetches past the end of `t` re-read its own last blocks
 // (three weight steps, two activation double steps), which nobody consumes.
-template <int W>
-__device__ __forceinline__ DmaTile<W> tail_alias(const DmaTile<W>& t, int KT) {
-  DmaTile<W> a = t;
+__device__ __forceinline__ DmaTile tail_alias(const DmaTile& t, int KT) {
+  DmaTile a = t;
   a.Wbase = t.Wbase + (size_t)(KT - 3) * kPackBlock;
   a.Abase = t.Abase + (size_t)((KT >> 1) - 2) * (kDmaBK * 4);
   return a;
 }
 
-// copy i of this wave's 16/W copies of the weights of k-step t into ring slot `slot` (1 KiB blocks wave + W i)
-template <int W>
+// copy i of this wave's four copies of the weights of k-step t into ring slot `slot` (1 KiB blocks wave + 4 i)
 __device__ __forceinline__ void issue_w1(const char* wbase, int t, int slot, int i, uint32_t lds0, int wave,
                                          int lane) {
   const char* wb = wbase + (size_t)t * kPackBlock;
   const uint32_t st = lds0 + kWRing + (uint32_t)slot * kWSlotBytes;
-  const uint32_t blk = (uint32_t)(wave + W * i) * 1024;
+  const uint32_t blk = (uint32_t)(wave + kDmaWaves * i) * 1024;
   dma_1k(wb, blk + lane * 16, st + blk);
 }
-template <int W>
 __device__ __forceinline__ void issue_w(const char* wbase, int t, int slot, uint32_t lds0, int wave, int lane) {
 #pragma unroll
-  for (int i = 0; i < 16 / W; ++i) issue_w1<W>(wbase, t, slot, i, lds0, wave, lane);
+  for (int i = 0; i < 16 / kDmaWaves; ++i) issue_w1(wbase, t, slot, i, lds0, wave, lane);
 }
-// copy j of this wave's 32/W copies of the activations of double step D into ring slot `slot` (blocks
-// wave + W j of 32, a block being 8 rows x 128 B)
-template <int W>
-__device__ __forceinline__ void issue_a1(const DmaTile<W>& t, int D, int slot, int j, uint32_t lds0, int wave) {
+// copy j of this wave's eight copies of the activations of double step D into ring slot `slot` (blocks
+// wave + 4 j of 32, a block being 8 rows x 128 B)
+__device__ __forceinline__ void issue_a1(const DmaTile& t, int D, int slot, int j, uint32_t lds0, int wave) {
   const char* ab = t.Abase + (size_t)D * (kDmaBK * 4);
   const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
-  dma_1k(ab, t.offA[j], st + (wave + W * j) * 1024);
+  dma_1k(ab, t.offA[j], st + (wave + kDmaWaves * j) * 1024);
 }
-template <int W>
-__device__ __forceinline__ void issue_a(const DmaTile<W>& t, int D, int slot, uint32_t lds0, int wave) {
+__device__ __forceinline__ void issue_a(const DmaTile& t, int D, int slot, uint32_t lds0, int wave) {
 #pragma unroll
-  for (int j = 0; j < DmaTile<W>::NA; ++j) issue_a1<W>(t, D, slot, j, lds0, wave);
+  for (int j = 0; j < DmaTile::NA; ++j) issue_a1(t, D, slot, j, lds0, wave);
 }
 
 // Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1) W(2), all landed and visible
 // to every wave on return.  Later tiles find the same state because the tile before them prefetched it.
-template <int W>
-__device__ __forceinline__ void dma_prefill(const DmaTile<W>& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
+__device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
   ring = DmaRing{0, 3, 0, 2};
-  issue_a<W>(t, 0, 0, lds0, wave);
-  issue_w<W>(t.Wbase, 0, 0, lds0, wave, lane);
-  issue_w<W>(t.Wbase, 1, 1, lds0, wave, lane);
-  issue_a<W>(t, 1, 1, lds0, wave);
-  issue_w<W>(t.Wbase, 2, 2, lds0, wave, lane);
+  issue_a(t, 0, 0, lds0, wave);
+  issue_w(t.Wbase, 0, 0, lds0, wave, lane);
+  issue_w(t.Wbase, 1, 1, lds0, wave, lane);
+  issue_a(t, 1, 1, lds0, wave);
+  issue_w(t.Wbase, 2, 2, lds0, wave, lane);
   wait_vmcnt<0>();
   __syncthreads();
 }
 
-// One output tile.  The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole 32-wide k-step of a
-// 16x16 output tile, and lane l always reads LDS chunk l/16 of its rows.  Measured on this part with random
-// bf16 operands, this shape sustains about 1.97 PFLOP/s against 1.47 PFLOP/s for the 32x32x16 shape (clock
-// management); LDS bytes per flop are identical for the two shapes at this wave tile.
+// One output tile.  Four waves, one per SIMD (2 along m x 2 along n, 128x128 per wave, the 256 accumulators
+// in the accumulation registers): 16 fragment reads feed 64 MFMAs per k-step.  (An eight-wave form, 128x64
+// per wave and two waves per SIMD, reads 12 fragments per 32 MFMAs: half as much again in LDS traffic, and
+// measured 3-4 % slower on both GEMMs.)  The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole
+// 32-wide k-step of a 16x16 output tile, and lane l always reads LDS chunk l/16 of its rows.  In pure MFMA loops
+// on random bf16 operands this shape sustains 1.73 PFLOP/s with one wave per SIMD (1.86 with two) against
+// 1.64 for the 32x32x16 shape (clock management).
+// With a single wave per SIMD nothing else hides the issue slots of the fragment reads and direct-to-LDS
+// copies, so they are interleaved one by one between the MFMAs.
+// Per wave and k-step: 4 weight copies, and 8 activation copies when the step is even; at the barrier of
+// step kt everything issued after the weights of kt+1 is 12 copies (either parity), hence vmcnt(12).
 //
 // On entry the first three weight steps and two activation double steps of `cur` are in the rings (landed and
 // published); the loop's prefetches run on into `nxt`, so on exit the same holds for `nxt` except that its
@@ -422,135 +411,8 @@ __device__ __forceinline__ void dma_prefill(const DmaTile<W>& t, DmaRing& ring, 
 // with vmcnt(0) before the next tile (stores and direct-to-LDS loads do not retire in order relative to
 // each other, so no smaller count is safe there).
 template <int NJ, bool GELU, class F>
-__device__ __forceinline__ void dma_tile(const DmaTile<8>& cur, const DmaTile<8>& nxt, DmaRing& ring,
+__device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
                                          uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
-                                         int lane, int wave, int ldc, F&& before_epilogue) {
-  // NJ = live 16-row activation subtiles of this wave
-  constexpr int NLO = NJ < 4 ? NJ : 4;        // first group of subtiles
-  constexpr int NHI = NJ - NLO;               // second group (0 for short tiles)
-  const int kq = lane >> 4, l16 = lane & 15;
-  lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
-  // subtile j of this wave: rows (2 j + wm)*16 .. +16 of the work-group tile (interleaved over the two wave rows);
-  // a_addr[half][j]: byte offset inside an activation slot for the even / odd k-step of a double step
-  int a_addr[2][8], b_addr[4];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int r = (2 * j + wm) * 16 + l16;
-    a_addr[0][j] = r * 128 + ((kq ^ ((r >> 1) & 7)) << 4);
-    a_addr[1][j] = r * 128 + (((4 + kq) ^ ((r >> 1) & 7)) << 4);
-  }
-#pragma unroll
-  for (int ni = 0; ni < 4; ++ni) {
-    const int r = wn * 64 + ni * 16 + l16;
-    b_addr[ni] = kWRing + r * 64 + ((kq ^ ((r >> 1) & 3)) << 4);
-  }
-  f32x4 acc[4][8];
-#pragma unroll
-  for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[ni][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-  const int KD = KT >> 1;  // double steps (KT is a multiple of 8)
-  bf16x8 fw[2][4], fa_lo[4], fa_hi[4];
-  auto load_w = [&](auto buf, int wslot) {
-    constexpr int B = decltype(buf)::value;
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
-      fw[B][ni] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)wslot * kWSlotBytes + b_addr[ni]);
-  };
-  auto load_lo = [&](auto half, int aslot) {
-    constexpr int H = decltype(half)::value;
-#pragma unroll
-    for (int j = 0; j < NLO; ++j)
-      fa_lo[j] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)aslot * kASlotBytes + a_addr[H][j]);
-  };
-  auto load_hi = [&](auto half, int aslot) {
-    constexpr int H = decltype(half)::value;
-#pragma unroll
-    for (int j = 0; j < NHI; ++j)
-      fa_hi[j] = *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)aslot * kASlotBytes + a_addr[H][4 + j]);
-  };
-  using I0 = std::integral_constant<int, 0>;
-  using I1 = std::integral_constant<int, 1>;
-  // (wave-uniform by construction; said explicitly so that the ring arithmetic stays on the scalar unit)
-  int wcur = __builtin_amdgcn_readfirstlane(ring.wcur), wfill = __builtin_amdgcn_readfirstlane(ring.wfill);
-  int acur = __builtin_amdgcn_readfirstlane(ring.acur), afill = __builtin_amdgcn_readfirstlane(ring.afill);
-
-  // One k-step; PAR = kt % 2.  On entry fw[PAR] and fa_lo hold the fragments of step kt; on exit fw[1-PAR] and
-  // fa_lo hold those of step kt+1.  The scheduling barriers keep every fragment read ahead of the MFMAs that
-  // run while it is in flight.
-  auto step = [&](auto par_, auto npar_, auto tail_, int kt) {
-    constexpr int PAR = decltype(par_)::value;
-    constexpr bool TAIL = decltype(tail_)::value;  // one of the tile's last four steps: prefetches may run over
-    const int wnxt = wcur + 1 == kWSlots ? 0 : wcur + 1;
-    const int anxt = PAR == 0 ? acur : (acur + 1 == kASlots ? 0 : acur + 1);  // slot of step kt+1's activations
-    load_hi(par_, acur);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NLO; ++j)
-#pragma unroll
-      for (int ni = 0; ni < 4; ++ni) acc[ni][j] = mfma16_bf16(fw[PAR][ni], fa_lo[j], acc[ni][j]);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<6>();   // weights of kt+1 (and, for odd kt, activations of double step (kt+1)/2) have landed
-    __syncthreads();   // ... for everybody; nobody reads weight slot kt-1 or, for even kt, activation slot kt/2-1
-    if (TAIL) {  // past this tile's end the stream runs on into the next tile
-      const int t = kt + 3;
-      const bool over = t >= KT;
-      issue_w<8>(over ? nxt.Wbase : cur.Wbase, over ? t - KT : t, wfill, lds0, wave, lane);
-      if (PAR == 0) issue_a<8>(nxt, (kt >> 1) + 2 - KD, afill, lds0, wave);  // kt = KT-4, KT-2
-    } else {
-      issue_w<8>(cur.Wbase, kt + 3, wfill, lds0, wave, lane);
-      if (PAR == 0) issue_a<8>(cur, (kt >> 1) + 2, afill, lds0, wave);
-    }
-    load_w(npar_, wnxt);       // (for kt+1 == KT: the next tile's first step, read again at its start)
-    load_lo(npar_, anxt);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NHI; ++j)
-#pragma unroll
-      for (int ni = 0; ni < 4; ++ni) acc[ni][4 + j] = mfma16_bf16(fw[PAR][ni], fa_hi[j], acc[ni][4 + j]);
-    __builtin_amdgcn_sched_barrier(0);
-    wcur = wnxt;
-    wfill = wfill + 1 == kWSlots ? 0 : wfill + 1;
-    if (PAR == 0) afill = afill + 1 == kASlots ? 0 : afill + 1;
-    acur = anxt;
-  };
-
-  load_w(I0{}, wcur);
-  load_lo(I0{}, acur);
-  for (int kt = 0; kt < KT - 4; kt += 2) {
-    step(I0{}, I1{}, std::false_type{}, kt);
-    step(I1{}, I0{}, std::false_type{}, kt + 1);
-  }
-  step(I0{}, I1{}, std::true_type{}, KT - 4);
-  step(I1{}, I0{}, std::true_type{}, KT - 3);
-  step(I0{}, I1{}, std::true_type{}, KT - 2);
-  step(I1{}, I0{}, std::true_type{}, KT - 1);
-  ring = DmaRing{wcur, wfill, acur, afill};
-  before_epilogue();  // (the persistent kernel starts its next claim here, to have the answer after the stores)
-
-#pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int m = (2 * j + wm) * 16 + l16;
-    if (m < cur.rows_left) {
-#pragma unroll
-      for (int ni = 0; ni < 4; ++ni) {
-        const int n = cur.n_base + wn * 64 + ni * 16 + kq * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
-        store_quad<GELU, false>(Cout, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
-      }
-    }
-  }
-}
-
-// The same tile with four waves, one per SIMD (2 along m x 2 along n, 128x128 per wave, 256 accumulator
-// registers): a third less LDS read traffic per flop than the eight-wave form (16 fragment reads feed 64
-// MFMAs instead of 12 feeding 32).  With a single wave per SIMD nothing else hides the issue slots of the
-// fragment reads and direct-to-LDS copies, so they are interleaved one by one between the MFMAs.
-// Per wave and k-step: 4 weight copies, and 8 activation copies when the step is even; at the barrier of
-// step kt everything issued after the weights of kt+1 is 12 copies (either parity), hence vmcnt(12).
-template <int NJ, bool GELU, class F>
-__device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4>& nxt, DmaRing& ring,
-                                          uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
                                           int lane, int wave, int ldc, F&& before_epilogue) {
   constexpr int NLO = NJ < 4 ? NJ : 4;
   constexpr int NHI = NJ - NLO;
@@ -562,7 +424,17 @@ __device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4
   const int a_base0 = ra * 128 + ((kq ^ ((ra >> 1) & 7)) << 4);
   const int a_base1 = ra * 128 + (((4 + kq) ^ ((ra >> 1) & 7)) << 4);
   const int b_base = kWRing + rb * 64 + ((kq ^ ((rb >> 1) & 3)) << 4);
-  f32x4 acc[8][8];  // written, not accumulated into, by the first k-step
+  // The accumulators are zeroed by MFMAs (0 x 0 + 0): the hardware orders an MFMA's result against the
+  // next MFMA that accumulates into it, which it does not do for a plain register write.
+  f32x4 acc[8][8];
+  {
+    bf16x8 zero = {};
+    asm volatile("s_nop 7" : "+v"(zero));  // (the zero operand is in its registers well before an MFMA reads it)
+#pragma unroll
+    for (int ni = 0; ni < 8; ++ni)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) mfma16_acc<true>(acc[ni][j], zero, zero);
+  }
 
   const int KD = KT >> 1;
   bf16x8 fw[2][8], fa_lo[4], fa_hi[4];
@@ -578,19 +450,21 @@ __device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4
   int wcur = __builtin_amdgcn_readfirstlane(ring.wcur), wfill = __builtin_amdgcn_readfirstlane(ring.wfill);
   int acur = __builtin_amdgcn_readfirstlane(ring.acur), afill = __builtin_amdgcn_readfirstlane(ring.afill);
 
-  auto step = [&](auto par_, auto tail_, auto first_, int kt) {
+  auto step = [&](auto par_, auto tail_, int kt) {
     constexpr int PAR = decltype(par_)::value;
-    constexpr bool FIRST = decltype(first_)::value;
     constexpr int NPAR = 1 - PAR;
-    constexpr bool TAIL = decltype(tail_)::value;
+    constexpr bool TAIL = decltype(tail_)::value;  // one of the tile's last four steps
     const int wnxt = wcur + 1 == kWSlots ? 0 : wcur + 1;
     const int anxt = PAR == 0 ? acur : (acur + 1 == kASlots ? 0 : acur + 1);
+    // (register copies that the compiler may place at a loop boundary are vector writes too: keep them a few
+    // wait states away from the MFMAs that read the fragments)
+    asm volatile("s_nop 3" ::: "memory");
     // first group of subtiles; the second group's activation fragments are read in between
 #pragma unroll
     for (int j = 0; j < NLO; ++j) {
       if (j < NHI) fa_hi[j] = read_a(PAR, 4 + j, acur);
 #pragma unroll
-      for (int ni = 0; ni < 8; ++ni) mfma16_acc<FIRST>(acc[ni][j], fw[PAR][ni], fa_lo[j]);
+      for (int ni = 0; ni < 8; ++ni) mfma16_acc<false>(acc[ni][j], fw[PAR][ni], fa_lo[j]);
       __builtin_amdgcn_sched_barrier(0);
     }
     wait_vmcnt<12>();  // weights of kt+1 (and, for odd kt, activations of double step (kt+1)/2) have landed
@@ -598,20 +472,27 @@ __device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4
     // second group of subtiles, with the other work spread between its MFMAs: the next step's fragment
     // reads first (needed soonest), then the copies of step kt+3 and, on even steps, double step kt/2+2
     constexpr int NREAD = 8 + NLO, NCOPY = 4 + (PAR == 0 ? 8 : 0), NITEM = NREAD + NCOPY, NM = NHI * 8;
+    // In the last four steps the prefetches run on into the next tile; those steps share one pair of bodies
+    // with run-time selects (a separate body per step pushed the eight loop variants out of the instruction
+    // cache: -3 % on the first GEMM, whose tiles are short), the steady state has none.
     const int tw = kt + 3;
     const bool w_over = TAIL && tw >= KT;
     const char* wsrc = w_over ? nxt.Wbase : cur.Wbase;
     const int wt = w_over ? tw - KT : tw;
-    const int aD = TAIL ? (kt >> 1) + 2 - KD : (kt >> 1) + 2;  // (even steps; the tail's two land in nxt)
+    const int aDD = (kt >> 1) + 2;  // (even steps)
+    const bool a_over = TAIL && aDD >= KD;
+    const char* asrc = (a_over ? nxt.Abase : cur.Abase) + (size_t)(a_over ? aDD - KD : aDD) * (kDmaBK * 4);
 #pragma unroll
     for (int i = 0; i < NITEM; ++i) {
       if (i < 8) fw[NPAR][i] = read_w(i, wnxt);
       else if (i < NREAD) fa_lo[i - 8] = read_a(NPAR, i - 8, anxt);
-      else if (i < NREAD + 4) issue_w1<4>(wsrc, wt, wfill, i - NREAD, lds0, wave, lane);
-      else issue_a1<4>(TAIL ? nxt : cur, aD, afill, i - NREAD - 4, lds0, wave);
+      else if (i < NREAD + 4) issue_w1(wsrc, wt, wfill, i - NREAD, lds0, wave, lane);
+      else
+        dma_1k(asrc, a_over ? nxt.offA[i - NREAD - 4] : cur.offA[i - NREAD - 4],
+               lds0 + (uint32_t)afill * kASlotBytes + (wave + 4 * (i - NREAD - 4)) * 1024);
 #pragma unroll
       for (int q = i * NM / NITEM; q < (i + 1) * NM / NITEM; ++q)
-        mfma16_acc<FIRST>(acc[q & 7][4 + (q >> 3)], fw[PAR][q & 7], fa_hi[q >> 3]);
+        mfma16_acc<false>(acc[q & 7][4 + (q >> 3)], fw[PAR][q & 7], fa_hi[q >> 3]);
       __builtin_amdgcn_sched_barrier(0);
     }
     wcur = wnxt;
@@ -624,16 +505,15 @@ __device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4
   for (int ni = 0; ni < 8; ++ni) fw[0][ni] = read_w(ni, wcur);
 #pragma unroll
   for (int j = 0; j < NLO; ++j) fa_lo[j] = read_a(0, j, acur);
-  step(I0{}, std::false_type{}, std::true_type{}, 0);
-  step(I1{}, std::false_type{}, std::false_type{}, 1);
-  for (int kt = 2; kt < KT - 4; kt += 2) {
-    step(I0{}, std::false_type{}, std::false_type{}, kt);
-    step(I1{}, std::false_type{}, std::false_type{}, kt + 1);
+  for (int kt = 0; kt < KT - 4; kt += 2) {
+    step(I0{}, std::false_type{}, kt);
+    step(I1{}, std::false_type{}, kt + 1);
   }
-  step(I0{}, std::true_type{}, std::false_type{}, KT - 4);
-  step(I1{}, std::true_type{}, std::false_type{}, KT - 3);
-  step(I0{}, std::true_type{}, std::false_type{}, KT - 2);
-  step(I1{}, std::true_type{}, std::false_type{}, KT - 1);
+#pragma nounroll
+  for (int kt = KT - 4; kt < KT; kt += 2) {
+    step(I0{}, std::true_type{}, kt);
+    step(I1{}, std::true_type{}, kt + 1);
+  }
   ring = DmaRing{wcur, wfill, acur, afill};
   __builtin_amdgcn_sched_barrier(0);  // (nothing that reads an accumulator may be scheduled above the wait states)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs have written their accumulators
@@ -655,16 +535,14 @@ __device__ __forceinline__ void dma_tile4(const DmaTile<4>& cur, const DmaTile<4
 
 // every variant executes the same loads and barriers; a wave row without live subtiles runs the
 // one-subtile variant on clamped rows and stores nothing
-template <bool GELU, int W, class F>
-__device__ __forceinline__ void dma_tile_any(const DmaTile<W>& cur, const DmaTile<W>& nxt, DmaRing& ring,
+template <bool GELU, class F>
+__device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
                                              uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int lane, int wave,
                                              int ldc, F&& before_epilogue) {
-  const int wm = W == 8 ? wave >> 2 : wave >> 1, wn = W == 8 ? wave & 3 : wave & 1;
+  const int wm = wave >> 1, wn = wave & 1;
   const int nsub = min(16, (cur.rows_left + 15) >> 4);  // live 16-row subtiles of this tile
   const int nj = __builtin_amdgcn_readfirstlane((nsub - wm + 1) >> 1);  // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
-#define LOCMOE_DMA_TILE(N)                                                                              \
-  if constexpr (W == 8) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue); \
-  else dma_tile4<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue)
+#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue)
   switch (nj) {
     case 8: LOCMOE_DMA_TILE(8); break;
     case 7: LOCMOE_DMA_TILE(7); break;
@@ -680,8 +558,8 @@ __device__ __forceinline__ void dma_tile_any(const DmaTile<W>& cur, const DmaTil
 
 // One tile per work-group, segments in buffer order: the shape of the grid for expert counts that the
 // persistent kernel below does not take.
-template <bool GELU, int W>
-__global__ __launch_bounds__(W * 64) void ffn_gemm_dma(const uint16_t* __restrict__ A,
+template <bool GELU>
+__global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __restrict__ A,
                                                             const uint16_t* __restrict__ Wp,
                                                             uint16_t* __restrict__ Cout,
                                                             const int32_t* __restrict__ seg_off,
@@ -697,11 +575,11 @@ __global__ __launch_bounds__(W * 64) void ffn_gemm_dma(const uint16_t* __restric
   if (mt * kBM >= rows) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const int KT = Kdim / kDmaBK;
-  const DmaTile<W> cur = make_tile<W>(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
-  const DmaTile<W> nxt = tail_alias<W>(cur, KT);
+  const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
+  const DmaTile nxt = tail_alias(cur, KT);
   DmaRing ring;
-  dma_prefill<W>(cur, ring, lds0, wave, lane);
-  dma_tile_any<GELU, W>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [] {});
+  dma_prefill(cur, ring, lds0, wave, lane);
+  dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [] {});
   wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
 }
 
@@ -739,8 +617,8 @@ __device__ __forceinline__ void leave_queues(unsigned int* queue, unsigned group
 // segment list in two registers (lane k: segment of local rank k and the inclusive tile count up to it;
 // E/8 <= 64), built once in LDS before the pipeline starts.  The claimed index reaches the other waves
 // through the one weight slot that is free between two tiles.
-template <bool GELU, int W>
-__global__ __launch_bounds__(W * 64) void ffn_gemm_dma_persistent(const uint16_t* __restrict__ A,
+template <bool GELU>
+__global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uint16_t* __restrict__ A,
                                                                        const uint16_t* __restrict__ Wp,
                                                                        uint16_t* __restrict__ Cout,
                                                                        const int32_t* __restrict__ seg_off,
@@ -754,9 +632,9 @@ __global__ __launch_bounds__(W * 64) void ffn_gemm_dma_persistent(const uint16_t
   const int nloc = E >> 3;  // segments of this XCD
   int32_t* s_seg = (int32_t*)smem;   // [E+1]
   int32_t* s_tab = s_seg + E + 1;    // [E/8]: segment of local rank k
-  for (int t = tid; t <= E; t += W * 64) s_seg[t] = seg_off[t];
+  for (int t = tid; t <= E; t += kDmaThreads) s_seg[t] = seg_off[t];
   __syncthreads();
-  for (int t = tid; t < E; t += W * 64) {
+  for (int t = tid; t < E; t += kDmaThreads) {
     const int mine = s_seg[t + 1] - s_seg[t];
     int rank = 0;
     for (int q = 0; q < E; ++q) {
@@ -799,13 +677,13 @@ __global__ __launch_bounds__(W * 64) void ffn_gemm_dma_persistent(const uint16_t
     const int within = jl - before;
     const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
     const int mtc = (rows + kBM - 1) / kBM;
-    return make_tile<W>(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim, wave, lane);
+    return make_tile(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim, wave, lane);
   };
   int claimed = 0;
   if (dynamic && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);  // the tile after the first
-  DmaTile<W> cur = tile_at(lb);
+  DmaTile cur = tile_at(lb);
   DmaRing ring;
-  dma_prefill<W>(cur, ring, lds0, wave, lane);
+  dma_prefill(cur, ring, lds0, wave, lane);
   for (;;) {
     // the claim goes from thread 0 to everybody through the weight slot that step 0 of `cur` refills, after
     // its barrier
@@ -814,8 +692,8 @@ __global__ __launch_bounds__(W * 64) void ffn_gemm_dma_persistent(const uint16_t
     __syncthreads();
     const int jn = dynamic ? stride + __builtin_amdgcn_readfirstlane(*mailbox) : total;
     const bool more = jn < total;
-    const DmaTile<W> nxt = more ? tile_at(jn) : tail_alias<W>(cur, KT);
-    dma_tile_any<GELU, W>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [&] {
+    const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KT);
+    dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [&] {
       if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
     });
     wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
@@ -868,20 +746,20 @@ int launch_dma(const void* A, const void* Wp, void* C, const int32_t* seg_off, c
   const long long total = (long long)E * MT * NT;
   if (total > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
   if (E % 8 == 0 && E <= 512) {
-    auto kern = ffn_gemm_dma_persistent<GELU, kDmaWaves<GELU>>;
+    auto kern = ffn_gemm_dma_persistent<GELU>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
       return LOCMOE_ERR_HIP;
     // one work-group per compute unit (160 KiB of LDS each), a multiple of 8 so that every XCD gets as many
     const long long groups = std::min<long long>((cu_count() / 8) * 8, (total + 7) / 8 * 8);
     const unsigned launch_id = next_launch_id();
-    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaWaves<GELU> * 64), kDmaSmem, st, (const uint16_t*)A,
+    hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
                        (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, NT, E, launch_id);
     return launch_status();
   }
-  auto kern = ffn_gemm_dma<GELU, kDmaWaves<GELU>>;
+  auto kern = ffn_gemm_dma<GELU>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
     return LOCMOE_ERR_HIP;
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaWaves<GELU> * 64), kDmaSmem, st, (const uint16_t*)A,
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
                      (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT);
   return launch_status();
 }
