@@ -250,26 +250,30 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 
 
 // ---------------------------------------------------------------------------------------------
-// DMA kernel: 256x256 tile, k-steps of 32, 8 waves (2 along m x 4 along n, 128x64 per wave).  Both
-// operands reach LDS by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers, no
+// DMA kernels: 256x256 tile, k-steps of 32 taken two at a time ("double steps"), four waves, one per
+// SIMD (2 along m x 2 along n, 128x128 per wave, the 256 accumulators in the accumulation registers).
+// Both operands reach LDS by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers, no
 // ds_write), in two rings that fill all 160 KiB of a CU:
-//   weights      4 slots x 16 KiB, one k-step each (256 rows x 64 B), from the packed layout: a
-//                work-group's weight stream is one contiguous run of 16 KiB blocks;
-//   activations  3 slots x 32 KiB, two k-steps each (256 rows x 128 B): rows are fetched as whole
-//                128-byte lines.  With 64-byte row segments every line was requested in two
-//                consecutive k-steps, and the per-CU vector-memory path is what bounds this kernel
-//                (measured: +5 % from whole lines alone).
+//   weights      3 slots x 32 KiB, one double step each: two consecutive 16 KiB blocks of the packed
+//                layout (256 rows x 64 B each), so a work-group's weight stream is one contiguous run;
+//   activations  2 slots x 32 KiB, one double step each (256 rows x 128 B): rows are fetched as whole
+//                128-byte lines (with 64-byte row segments every line was requested in two consecutive
+//                k-steps: +5 % from whole lines alone).
+// Weights come from HBM and are issued two double steps ahead, activations mostly from L2 and one ahead.
 //
 // A direct-to-LDS load writes lane l's 16 bytes at base + 16 l, so the LDS image is produced by
 // choosing which global chunk each lane fetches.  Slot functions (measured conflict-free for the
 // 16x16x32 fragment read, lane l: row l%16, chunk l/16): 64-byte weight rows: chunk ^ (row/2 mod 4);
 // 128-byte activation rows: chunk ^ (row/2 mod 8).
 //
+// One barrier per double step D, between the two MFMA groups of its second k-step.  By then every wave
+// has issued all its fragment reads of double step D, so behind the barrier the slots of W(D) and A(D)
+// are refilled: A(D+2) at once, W(D+3) during the next k-step (a slot ahead of need either way).  The
+// barrier also publishes W(D+1) and A(D+1), whose first fragments are read right behind it.
 // The compiler does not know about these loads (inline asm), so the vmcnt accounting is explicit:
-// loads complete in order and nothing else in the K loop uses vmcnt.  Per wave, k-step kt issues
-// the 2 weight loads of step kt+3 and, when kt is even, the 4 activation loads of double step
-// kt/2+2.  At the barrier of step kt the weights of kt+1 (and, for odd kt, the activations of double
-// step (kt+1)/2) must have landed; everything issued after them is 6 loads, hence vmcnt(6).
+// direct-to-LDS loads complete in order and nothing else in the K loop uses vmcnt.  Per wave a double
+// step issues 8 weight and 8 activation copies; at the barrier of D everything issued after A(D+1) is
+// the 8 copies of W(D+2), hence vmcnt(8).
 //
 // Rows of the tile are owned in interleaved 16-row subtiles (wave row wm owns subtiles wm, wm+2,
 // ...), so a ragged tile skips MFMAs evenly across waves, at 32-row granularity overall.
@@ -277,11 +281,11 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 constexpr int kDmaBK = 32;
 constexpr int kDmaWaves = 4;               // one wave per SIMD
 constexpr int kDmaThreads = kDmaWaves * 64;
-constexpr int kWSlots = 4, kWSlotBytes = kBN * kDmaBK * 2;     // 4 x 16 KiB
-constexpr int kASlots = 3, kASlotBytes = kBM * kDmaBK * 2 * 2;  // 3 x 32 KiB
+constexpr int kPackBlock = kBN * kDmaBK * 2;                    // 16 KiB: one packed weight block (one k-step)
+constexpr int kWSlots = 3, kWSlotBytes = 2 * kPackBlock;        // 3 x 32 KiB
+constexpr int kASlots = 2, kASlotBytes = kBM * kDmaBK * 2 * 2;  // 2 x 32 KiB
 constexpr int kWRing = kASlots * kASlotBytes;                   // weights ring starts after the activations ring
 constexpr int kDmaSmem = kWRing + kWSlots * kWSlotBytes;        // 160 KiB: the whole LDS of a CU
-constexpr int kPackBlock = kWSlotBytes;                         // 16 KiB: one packed weight block
 
 typedef const char __attribute__((address_space(3))) * lds_cptr;
 
@@ -316,20 +320,18 @@ __device__ __forceinline__ void mfma16_acc(f32x4& c, const bf16x8& a, const bf16
 
 // What the pipeline needs to know about one 256x256 output tile.
 struct DmaTile {
-  static constexpr int NA = 32 / kDmaWaves;  // 1 KiB activation copies per wave and double step
   const char* Abase;   // first activation row of the tile
   const char* Wbase;   // first packed block of the tile's 256 weight rows (output columns)
-  uint32_t offA[NA];   // per-lane source offsets of this wave's activation copies
+  uint32_t offA[8];    // per-lane source offsets of this wave's eight 1 KiB activation copies
   int rows_left;       // live rows from the tile's first row to the segment's end (>= 1)
   size_t crow0;        // first output row
   int n_base;          // first output column
 };
-// Ring positions, carried from tile to tile: weight slot of the current k-step and the slot that the
-// k-step three ahead goes to; activation slot of the current double step and the slot two ahead.
-struct DmaRing { int wcur, wfill, acur, afill; };
+// Ring positions, carried from tile to tile: the slots of the current double step's weights and activations.
+struct DmaRing { int wcur, acur; };
 
 __device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
-                                                int nt, int e, int Kdim, int Ndim, int wave, int lane) {
+                                             int nt, int e, int Kdim, int Ndim, int wave, int lane) {
   DmaTile t;
   const int m0 = mt * kBM;
   t.rows_left = rows - m0;
@@ -338,7 +340,7 @@ __device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* 
   // lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS chunk l%8 receives source chunk
   // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
 #pragma unroll
-  for (int j = 0; j < DmaTile::NA; ++j) {
+  for (int j = 0; j < 8; ++j) {
     const int row = 8 * (wave + kDmaWaves * j) + (lane >> 3);
     const int kc = (lane & 7) ^ ((row >> 1) & 7);
     t.offA[j] = (uint32_t)min(row, t.rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
@@ -347,82 +349,70 @@ __device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* 
   t.n_base = nt * kBN;
   return t;
 }
-// Stand-in for "the tile after the last": prefetches past the end of `t` re-read its own last blocks
-// (three weight steps, two activation double steps), which nobody consumes.
-__device__ __forceinline__ DmaTile tail_alias(const DmaTile& t, int KT) {
+// Stand-in for "the tile after the last": prefetches past the end of `t` re-read its own last two double
+// steps, which nobody consumes.
+__device__ __forceinline__ DmaTile tail_alias(const DmaTile& t, int KD) {
   DmaTile a = t;
-  a.Wbase = t.Wbase + (size_t)(KT - 3) * kPackBlock;
-  a.Abase = t.Abase + (size_t)((KT >> 1) - 2) * (kDmaBK * 4);
+  a.Wbase = t.Wbase + (size_t)(KD - 2) * kWSlotBytes;
+  a.Abase = t.Abase + (size_t)(KD - 2) * (kDmaBK * 4);
   return a;
 }
 
-// copy i of this wave's four copies of the weights of k-step t into ring slot `slot` (1 KiB blocks wave + 4 i)
-__device__ __forceinline__ void issue_w1(const char* wbase, int t, int slot, int i, uint32_t lds0, int wave,
+// copy i (of this wave's eight) of the weights of double step D into ring slot `slot`: 1 KiB block wave + 4 i of 32
+__device__ __forceinline__ void issue_w1(const char* wbase, int D, int slot, int i, uint32_t lds0, int wave,
                                          int lane) {
-  const char* wb = wbase + (size_t)t * kPackBlock;
-  const uint32_t st = lds0 + kWRing + (uint32_t)slot * kWSlotBytes;
+  const char* wb = wbase + (size_t)D * kWSlotBytes;
   const uint32_t blk = (uint32_t)(wave + kDmaWaves * i) * 1024;
-  dma_1k(wb, blk + lane * 16, st + blk);
+  dma_1k(wb, blk + lane * 16, lds0 + kWRing + (uint32_t)slot * kWSlotBytes + blk);
 }
-__device__ __forceinline__ void issue_w(const char* wbase, int t, int slot, uint32_t lds0, int wave, int lane) {
-#pragma unroll
-  for (int i = 0; i < 16 / kDmaWaves; ++i) issue_w1(wbase, t, slot, i, lds0, wave, lane);
-}
-// copy j of this wave's eight copies of the activations of double step D into ring slot `slot` (blocks
-// wave + 4 j of 32, a block being 8 rows x 128 B)
-__device__ __forceinline__ void issue_a1(const DmaTile& t, int D, int slot, int j, uint32_t lds0, int wave) {
-  const char* ab = t.Abase + (size_t)D * (kDmaBK * 4);
-  const uint32_t st = lds0 + (uint32_t)slot * kASlotBytes;
-  dma_1k(ab, t.offA[j], st + (wave + kDmaWaves * j) * 1024);
-}
-__device__ __forceinline__ void issue_a(const DmaTile& t, int D, int slot, uint32_t lds0, int wave) {
-#pragma unroll
-  for (int j = 0; j < DmaTile::NA; ++j) issue_a1(t, D, slot, j, lds0, wave);
+// copy j (of this wave's eight) of the activations of double step D into ring slot `slot`: block wave + 4 j of
+// 32, a block being 8 rows x 128 B
+__device__ __forceinline__ void issue_a1(const char* abase, uint32_t off, int D, int slot, int j, uint32_t lds0,
+                                         int wave) {
+  dma_1k(abase + (size_t)D * (kDmaBK * 4), off, lds0 + (uint32_t)slot * kASlotBytes + (wave + kDmaWaves * j) * 1024);
 }
 
-// Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1) W(2), all landed and visible
-// to every wave on return.  Later tiles find the same state because the tile before them prefetched it.
+// Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1), all landed and visible to
+// every wave on return.  Later tiles find the same state because the tile before them prefetched it.
 __device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
-  ring = DmaRing{0, 3, 0, 2};
-  issue_a(t, 0, 0, lds0, wave);
-  issue_w(t.Wbase, 0, 0, lds0, wave, lane);
-  issue_w(t.Wbase, 1, 1, lds0, wave, lane);
-  issue_a(t, 1, 1, lds0, wave);
-  issue_w(t.Wbase, 2, 2, lds0, wave, lane);
+  ring = DmaRing{0, 0};
+#pragma unroll
+  for (int D = 0; D < 2; ++D) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) issue_a1(t.Abase, t.offA[j], D, D, j, lds0, wave);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) issue_w1(t.Wbase, D, D, i, lds0, wave, lane);
+  }
   wait_vmcnt<0>();
   __syncthreads();
 }
 
-// One output tile.  Four waves, one per SIMD (2 along m x 2 along n, 128x128 per wave, the 256 accumulators
-// in the accumulation registers): 16 fragment reads feed 64 MFMAs per k-step.  (An eight-wave form, 128x64
-// per wave and two waves per SIMD, reads 12 fragments per 32 MFMAs: half as much again in LDS traffic, and
-// measured 3-4 % slower on both GEMMs.)  The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole
-// 32-wide k-step of a 16x16 output tile, and lane l always reads LDS chunk l/16 of its rows.  In pure MFMA loops
-// on random bf16 operands this shape sustains 1.73 PFLOP/s with one wave per SIMD (1.86 with two) against
-// 1.64 for the 32x32x16 shape (clock management).
-// With a single wave per SIMD nothing else hides the issue slots of the fragment reads and direct-to-LDS
-// copies, so they are interleaved one by one between the MFMAs.
-// Per wave and k-step: 4 weight copies, and 8 activation copies when the step is even; at the barrier of
-// step kt everything issued after the weights of kt+1 is 12 copies (either parity), hence vmcnt(12).
+// One output tile.  16 fragment reads feed 64 MFMAs per k-step.  (An eight-wave form, 128x64 per wave and
+// two waves per SIMD, reads 12 fragments per 32 MFMAs: half as much again in LDS traffic, and measured
+// 3-4 % slower on both GEMMs.)  The K loop uses v_mfma_f32_16x16x32_bf16: one MFMA consumes a whole 32-wide
+// k-step of a 16x16 output tile, and lane l always reads LDS chunk l/16 of its rows.  In pure MFMA loops on
+// random bf16 operands this shape sustains 1.73 PFLOP/s with one wave per SIMD (1.86 with two) against 1.64
+// for the 32x32x16 shape (clock management).  With a single wave per SIMD nothing else hides the issue
+// slots of the fragment reads and direct-to-LDS copies, so they are interleaved one by one between the MFMAs.
 //
-// On entry the first three weight steps and two activation double steps of `cur` are in the rings (landed and
-// published); the loop's prefetches run on into `nxt`, so on exit the same holds for `nxt` except that its
-// last prefetches (W(1), W(2), A(1)) and this tile's stores may still be in flight: the caller drains them
-// with vmcnt(0) before the next tile (stores and direct-to-LDS loads do not retire in order relative to
-// each other, so no smaller count is safe there).
+// On entry W(0), W(1), A(0) of `cur` have landed and are published and A(1) is in flight or landed; the
+// loop's prefetches run on into `nxt`, so on exit the same holds for `nxt`, and this tile's stores may
+// still be in flight: the caller drains everything with vmcnt(0) before the next tile (stores and
+// direct-to-LDS loads do not retire in order relative to each other, so no smaller count is safe there).
 template <int NJ, bool GELU, class F>
 __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
-                                         uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int wm, int wn,
-                                          int lane, int wave, int ldc, F&& before_epilogue) {
-  constexpr int NLO = NJ < 4 ? NJ : 4;
-  constexpr int NHI = NJ - NLO;
+                                         uint16_t* __restrict__ Cout, uint32_t lds0, int KD, int wm, int wn,
+                                         int lane, int wave, int ldc, F&& before_epilogue) {
+  // NJ = live 16-row activation subtiles of this wave
+  constexpr int NLO = NJ < 4 ? NJ : 4;        // first group of subtiles
+  constexpr int NHI = NJ - NLO;               // second group (0 for short tiles)
   const int kq = lane >> 4, l16 = lane & 15;
   lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
   // subtile j of this wave: rows (2 j + wm)*16 .. +16; weight subtile ni: rows wn*128 + ni*16 .. +16.  The
   // swizzle terms do not depend on j or ni, so the per-subtile addresses are constant offsets from these.
   const int ra = wm * 16 + l16, rb = wn * 128 + l16;
-  const int a_base0 = ra * 128 + ((kq ^ ((ra >> 1) & 7)) << 4);
-  const int a_base1 = ra * 128 + (((4 + kq) ^ ((ra >> 1) & 7)) << 4);
+  const int a_base0 = ra * 128 + ((kq ^ ((ra >> 1) & 7)) << 4);        // first k-step of a double step
+  const int a_base1 = ra * 128 + (((4 + kq) ^ ((ra >> 1) & 7)) << 4);  // second
   const int b_base = kWRing + rb * 64 + ((kq ^ ((rb >> 1) & 3)) << 4);
   // The accumulators are zeroed by MFMAs (0 x 0 + 0): the hardware orders an MFMA's result against the
   // next MFMA that accumulates into it, which it does not do for a plain register write.
@@ -436,10 +426,10 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
       for (int j = 0; j < NJ; ++j) mfma16_acc<true>(acc[ni][j], zero, zero);
   }
 
-  const int KD = KT >> 1;
   bf16x8 fw[2][8], fa_lo[4], fa_hi[4];
-  auto read_w = [&](int ni, int wslot) {
-    return *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)wslot * kWSlotBytes + b_base + ni * 1024);
+  auto read_w = [&](int half, int ni, int wslot) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)wslot * kWSlotBytes + half * kPackBlock +
+                                                                b_base + ni * 1024);
   };
   auto read_a = [&](int half, int j, int aslot) {
     return *(const bf16x8 __attribute__((address_space(3)))*)(lds + (uint32_t)aslot * kASlotBytes +
@@ -447,15 +437,15 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
-  int wcur = __builtin_amdgcn_readfirstlane(ring.wcur), wfill = __builtin_amdgcn_readfirstlane(ring.wfill);
-  int acur = __builtin_amdgcn_readfirstlane(ring.acur), afill = __builtin_amdgcn_readfirstlane(ring.afill);
+  // (wave-uniform by construction; said explicitly so that the ring arithmetic stays on the scalar unit)
+  int wcur = __builtin_amdgcn_readfirstlane(ring.wcur), acur = __builtin_amdgcn_readfirstlane(ring.acur);
 
-  auto step = [&](auto par_, auto tail_, int kt) {
+  // One k-step of double step D; PAR = which of its two.  On entry fw[PAR] and fa_lo hold the fragments of
+  // this k-step; on exit fw[1-PAR] and fa_lo hold those of the next.
+  auto step = [&](auto par_, auto tail_, int D) {
     constexpr int PAR = decltype(par_)::value;
     constexpr int NPAR = 1 - PAR;
-    constexpr bool TAIL = decltype(tail_)::value;  // one of the tile's last four steps
-    const int wnxt = wcur + 1 == kWSlots ? 0 : wcur + 1;
-    const int anxt = PAR == 0 ? acur : (acur + 1 == kASlots ? 0 : acur + 1);
+    constexpr bool TAIL = decltype(tail_)::value;  // one of the tile's last two double steps
     // (register copies that the compiler may place at a loop boundary are vector writes too: keep them a few
     // wait states away from the MFMAs that read the fragments)
     asm volatile("s_nop 3" ::: "memory");
@@ -467,54 +457,56 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
       for (int ni = 0; ni < 8; ++ni) mfma16_acc<false>(acc[ni][j], fw[PAR][ni], fa_lo[j]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_vmcnt<12>();  // weights of kt+1 (and, for odd kt, activations of double step (kt+1)/2) have landed
-    __syncthreads();   // ... for everybody; nobody reads weight slot kt-1 or, for even kt, activation slot kt/2-1
-    // second group of subtiles, with the other work spread between its MFMAs: the next step's fragment
-    // reads first (needed soonest), then the copies of step kt+3 and, on even steps, double step kt/2+2
-    constexpr int NREAD = 8 + NLO, NCOPY = 4 + (PAR == 0 ? 8 : 0), NITEM = NREAD + NCOPY, NM = NHI * 8;
-    // In the last four steps the prefetches run on into the next tile; those steps share one pair of bodies
-    // with run-time selects (a separate body per step pushed the eight loop variants out of the instruction
-    // cache: -3 % on the first GEMM, whose tiles are short), the steady state has none.
-    const int tw = kt + 3;
-    const bool w_over = TAIL && tw >= KT;
-    const char* wsrc = w_over ? nxt.Wbase : cur.Wbase;
-    const int wt = w_over ? tw - KT : tw;
-    const int aDD = (kt >> 1) + 2;  // (even steps)
-    const bool a_over = TAIL && aDD >= KD;
-    const char* asrc = (a_over ? nxt.Abase : cur.Abase) + (size_t)(a_over ? aDD - KD : aDD) * (kDmaBK * 4);
+    const int wnext = wcur + 1 == kWSlots ? 0 : wcur + 1;
+    if (PAR == 1) {
+      wait_vmcnt<8>();   // W(D+1) and A(D+1) have landed (this wave's share)
+      __syncthreads();   // ... and everybody's; nobody reads the slots of W(D) and A(D) any more
+    }
+    // second group of subtiles, with the other work spread between its MFMAs: the next k-step's fragment
+    // reads first (needed soonest), then eight copies: W(D+2) in the first k-step (into the slot that the
+    // previous barrier freed), A(D+2) in the second (into the slot that this barrier freed).
+    // In the last two double steps the copies run on into the next tile; those steps share one pair of
+    // bodies with run-time selects (a separate body per step pushed the eight loop variants out of the
+    // instruction cache: -3 % on the first GEMM, whose tiles are short), the steady state has none.
+    constexpr int NREAD = 8 + NLO, NITEM = NREAD + 8, NM = NHI * 8;
+    const bool over = TAIL && D + 2 >= KD;
+    const int Dsrc = over ? D + 2 - KD : D + 2;
+    const char* wsrc = over ? nxt.Wbase : cur.Wbase;
+    const char* asrc = over ? nxt.Abase : cur.Abase;
+    const int wslot2 = wnext + 1 == kWSlots ? 0 : wnext + 1;  // slot of W(D+2) = slot of W(D-1)
+    const int rslot_w = PAR == 0 ? wcur : wnext;              // where the next k-step's fragments are
+    const int rslot_a = PAR == 0 ? acur : acur ^ 1;
 #pragma unroll
     for (int i = 0; i < NITEM; ++i) {
-      if (i < 8) fw[NPAR][i] = read_w(i, wnxt);
-      else if (i < NREAD) fa_lo[i - 8] = read_a(NPAR, i - 8, anxt);
-      else if (i < NREAD + 4) issue_w1(wsrc, wt, wfill, i - NREAD, lds0, wave, lane);
-      else
-        dma_1k(asrc, a_over ? nxt.offA[i - NREAD - 4] : cur.offA[i - NREAD - 4],
-               lds0 + (uint32_t)afill * kASlotBytes + (wave + 4 * (i - NREAD - 4)) * 1024);
+      if (i < 8) fw[NPAR][i] = read_w(NPAR, i, rslot_w);
+      else if (i < NREAD) fa_lo[i - 8] = read_a(NPAR, i - 8, rslot_a);
+      else if (PAR == 0) issue_w1(wsrc, Dsrc, wslot2, i - NREAD, lds0, wave, lane);
+      else issue_a1(asrc, over ? nxt.offA[i - NREAD] : cur.offA[i - NREAD], Dsrc, acur, i - NREAD, lds0, wave);
 #pragma unroll
       for (int q = i * NM / NITEM; q < (i + 1) * NM / NITEM; ++q)
         mfma16_acc<false>(acc[q & 7][4 + (q >> 3)], fw[PAR][q & 7], fa_hi[q >> 3]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    wcur = wnxt;
-    wfill = wfill + 1 == kWSlots ? 0 : wfill + 1;
-    if (PAR == 0) afill = afill + 1 == kASlots ? 0 : afill + 1;
-    acur = anxt;
+    if (PAR == 1) {
+      wcur = wnext;
+      acur ^= 1;
+    }
   };
 
 #pragma unroll
-  for (int ni = 0; ni < 8; ++ni) fw[0][ni] = read_w(ni, wcur);
+  for (int ni = 0; ni < 8; ++ni) fw[0][ni] = read_w(0, ni, wcur);
 #pragma unroll
   for (int j = 0; j < NLO; ++j) fa_lo[j] = read_a(0, j, acur);
-  for (int kt = 0; kt < KT - 4; kt += 2) {
-    step(I0{}, std::false_type{}, kt);
-    step(I1{}, std::false_type{}, kt + 1);
+  for (int D = 0; D < KD - 2; ++D) {
+    step(I0{}, std::false_type{}, D);
+    step(I1{}, std::false_type{}, D);
   }
 #pragma nounroll
-  for (int kt = KT - 4; kt < KT; kt += 2) {
-    step(I0{}, std::true_type{}, kt);
-    step(I1{}, std::true_type{}, kt + 1);
+  for (int D = KD - 2; D < KD; ++D) {
+    step(I0{}, std::true_type{}, D);
+    step(I1{}, std::true_type{}, D);
   }
-  ring = DmaRing{wcur, wfill, acur, afill};
+  ring = DmaRing{wcur, acur};
   __builtin_amdgcn_sched_barrier(0);  // (nothing that reads an accumulator may be scheduled above the wait states)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs have written their accumulators
   __builtin_amdgcn_sched_barrier(0);
@@ -526,7 +518,7 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
     if (m < cur.rows_left) {
 #pragma unroll
       for (int ni = 0; ni < 8; ++ni) {
-        const int n = cur.n_base + wn * 128 + ni * 16 + kq * 4;
+        const int n = cur.n_base + wn * 128 + ni * 16 + kq * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
         store_quad<GELU, false>(Cout, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
       }
     }
@@ -537,12 +529,12 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
 // one-subtile variant on clamped rows and stores nothing
 template <bool GELU, class F>
 __device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
-                                             uint16_t* __restrict__ Cout, uint32_t lds0, int KT, int lane, int wave,
+                                             uint16_t* __restrict__ Cout, uint32_t lds0, int KD, int lane, int wave,
                                              int ldc, F&& before_epilogue) {
   const int wm = wave >> 1, wn = wave & 1;
   const int nsub = min(16, (cur.rows_left + 15) >> 4);  // live 16-row subtiles of this tile
   const int nj = __builtin_amdgcn_readfirstlane((nsub - wm + 1) >> 1);  // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
-#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KT, wm, wn, lane, wave, ldc, before_epilogue)
+#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KD, wm, wn, lane, wave, ldc, before_epilogue)
   switch (nj) {
     case 8: LOCMOE_DMA_TILE(8); break;
     case 7: LOCMOE_DMA_TILE(7); break;
@@ -574,12 +566,12 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
   if (mt * kBM >= rows) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-  const int KT = Kdim / kDmaBK;
+  const int KD = Kdim / (2 * kDmaBK);  // double steps
   const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
-  const DmaTile nxt = tail_alias(cur, KT);
+  const DmaTile nxt = tail_alias(cur, KD);
   DmaRing ring;
   dma_prefill(cur, ring, lds0, wave, lane);
-  dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [] {});
+  dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KD, lane, wave, Ndim, [] {});
   wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
 }
 
@@ -669,7 +661,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
   }
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-  const int KT = Kdim / kDmaBK;
+  const int KD = Kdim / (2 * kDmaBK);  // double steps
   auto tile_at = [&](int jl) {
     const int k = __builtin_popcountll(__ballot(tab_cum <= jl));  // local rank of the segment that holds tile jl
     const int r = __builtin_amdgcn_readfirstlane(__shfl(tab_seg, k, 64));
@@ -685,15 +677,17 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
   DmaRing ring;
   dma_prefill(cur, ring, lds0, wave, lane);
   for (;;) {
-    // the claim goes from thread 0 to everybody through the weight slot that step 0 of `cur` refills, after
-    // its barrier
-    volatile int* mailbox = (volatile int*)(smem + kWRing + ring.wfill * kWSlotBytes);
+    // the claim goes from thread 0 to everybody through the one weight slot that is free between two tiles
+    // (the tile's first k-step refills it: hence the second barrier)
+    const int wfree = ring.wcur + 2 >= kWSlots ? ring.wcur + 2 - kWSlots : ring.wcur + 2;
+    volatile int* mailbox = (volatile int*)(smem + kWRing + wfree * kWSlotBytes);
     if (tid == 0) *mailbox = claimed;
     __syncthreads();
     const int jn = dynamic ? stride + __builtin_amdgcn_readfirstlane(*mailbox) : total;
+    __syncthreads();
     const bool more = jn < total;
-    const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KT);
-    dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KT, lane, wave, Ndim, [&] {
+    const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KD);
+    dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KD, lane, wave, Ndim, [&] {
       if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
     });
     wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
