@@ -512,13 +512,18 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
   __builtin_amdgcn_sched_barrier(0);
   before_epilogue();
 
+  // The store addresses are formed here, from lane indices that the compiler cannot trace back across the
+  // K loop: computed ahead of it they were spilled, and every row of the epilogue began with a reload from
+  // scratch memory (13 us per tile, with one wave per SIMD to hide it).
+  int l16e = l16, kqe = kq;
+  asm volatile("" : "+v"(l16e), "+v"(kqe));
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int m = (2 * j + wm) * 16 + l16;
+    const int m = (2 * j + wm) * 16 + l16e;
     if (m < cur.rows_left) {
 #pragma unroll
       for (int ni = 0; ni < 8; ++ni) {
-        const int n = cur.n_base + wn * 128 + ni * 16 + kq * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
+        const int n = cur.n_base + wn * 128 + ni * 16 + kqe * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
         store_quad<GELU, false>(Cout, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
       }
     }
