@@ -318,33 +318,37 @@ __device__ __forceinline__ void mfma16_acc(f32x4& c, const bf16x8& a, const bf16
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
-// What the pipeline needs to know about one 256x256 output tile.
+// What the pipeline needs to know about one 256x256 output tile (all wave-uniform).
 struct DmaTile {
   const char* Abase;   // first activation row of the tile
   const char* Wbase;   // first packed block of the tile's 256 weight rows (output columns)
-  uint32_t offA[8];    // per-lane source offsets of this wave's eight 1 KiB activation copies
   int rows_left;       // live rows from the tile's first row to the segment's end (>= 1)
   size_t crow0;        // first output row
   int n_base;          // first output column
 };
 // Ring positions, carried from tile to tile: the slots of the current double step's weights and activations.
 struct DmaRing { int wcur, acur; };
+// What a lane contributes to the activation copies.  Lane l of the copy of row block b (8 rows x 128 B)
+// fetches row 8 b + l/8; LDS chunk l%8 receives source chunk (l%8) ^ (row/2 mod 8), which is the same for
+// all of a wave's blocks (they are 32 rows apart).  Rows past the segment's end re-read its last row
+// (results masked at the store).
+struct DmaLane {
+  uint32_t row0;       // row of this lane in the wave's first block
+  uint32_t chunk16;    // byte offset of its source chunk inside a 128-byte row segment
+  uint32_t row_bytes;  // bytes per activation row
+};
+__device__ __forceinline__ DmaLane make_lane(int Kdim, int wave, int lane) {
+  const uint32_t row0 = 8 * wave + (lane >> 3);
+  return DmaLane{row0, (uint32_t)(((lane & 7) ^ ((row0 >> 1) & 7)) * 16), (uint32_t)Kdim * 2u};
+}
 
 __device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
-                                             int nt, int e, int Kdim, int Ndim, int wave, int lane) {
+                                             int nt, int e, int Kdim, int Ndim) {
   DmaTile t;
   const int m0 = mt * kBM;
   t.rows_left = rows - m0;
   t.Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
   t.Wbase = (const char*)(Wp + ((size_t)e * Ndim + (size_t)nt * kBN) * (size_t)Kdim);
-  // lane l of the copy of row block b (8 rows x 128 B): row 8 b + l/8, LDS chunk l%8 receives source chunk
-  // (l%8) ^ (row/2 mod 8).  Rows past the segment's end re-read its last row (results masked at the store).
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int row = 8 * (wave + kDmaWaves * j) + (lane >> 3);
-    const int kc = (lane & 7) ^ ((row >> 1) & 7);
-    t.offA[j] = (uint32_t)min(row, t.rows_left - 1) * (uint32_t)(Kdim * 2) + kc * 16;
-  }
   t.crow0 = (size_t)seg0 + m0;
   t.n_base = nt * kBN;
   return t;
@@ -367,19 +371,22 @@ __device__ __forceinline__ void issue_w1(const char* wbase, int D, int slot, int
 }
 // copy j (of this wave's eight) of the activations of double step D into ring slot `slot`: block wave + 4 j of
 // 32, a block being 8 rows x 128 B
-__device__ __forceinline__ void issue_a1(const char* abase, uint32_t off, int D, int slot, int j, uint32_t lds0,
+__device__ __forceinline__ void issue_a1(const DmaTile& t, const DmaLane& ln, int D, int slot, int j, uint32_t lds0,
                                          int wave) {
-  dma_1k(abase + (size_t)D * (kDmaBK * 4), off, lds0 + (uint32_t)slot * kASlotBytes + (wave + kDmaWaves * j) * 1024);
+  const uint32_t row = min(ln.row0 + 32u * j, (uint32_t)t.rows_left - 1u);
+  dma_1k(t.Abase + (size_t)D * (kDmaBK * 4), row * ln.row_bytes + ln.chunk16,
+         lds0 + (uint32_t)slot * kASlotBytes + (wave + kDmaWaves * j) * 1024);
 }
 
 // Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1), all landed and visible to
 // every wave on return.  Later tiles find the same state because the tile before them prefetched it.
-__device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uint32_t lds0, int wave, int lane) {
+__device__ __forceinline__ void dma_prefill(const DmaTile& t, const DmaLane& ln, DmaRing& ring, uint32_t lds0, int wave,
+                                            int lane) {
   ring = DmaRing{0, 0};
 #pragma unroll
   for (int D = 0; D < 2; ++D) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) issue_a1(t.Abase, t.offA[j], D, D, j, lds0, wave);
+    for (int j = 0; j < 8; ++j) issue_a1(t, ln, D, D, j, lds0, wave);
 #pragma unroll
     for (int i = 0; i < 8; ++i) issue_w1(t.Wbase, D, D, i, lds0, wave, lane);
   }
@@ -400,7 +407,7 @@ __device__ __forceinline__ void dma_prefill(const DmaTile& t, DmaRing& ring, uin
 // still be in flight: the caller drains everything with vmcnt(0) before the next tile (stores and
 // direct-to-LDS loads do not retire in order relative to each other, so no smaller count is safe there).
 template <int NJ, bool GELU, class F>
-__device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
+__device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, const DmaLane& ln, DmaRing& ring,
                                          uint16_t* __restrict__ Cout, uint32_t lds0, int KD, int wm, int wn,
                                          int lane, int wave, int ldc, F&& before_epilogue) {
   // NJ = live 16-row activation subtiles of this wave
@@ -472,7 +479,6 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
     const bool over = TAIL && D + 2 >= KD;
     const int Dsrc = over ? D + 2 - KD : D + 2;
     const char* wsrc = over ? nxt.Wbase : cur.Wbase;
-    const char* asrc = over ? nxt.Abase : cur.Abase;
     const int wslot2 = wnext + 1 == kWSlots ? 0 : wnext + 1;  // slot of W(D+2) = slot of W(D-1)
     const int rslot_w = PAR == 0 ? wcur : wnext;              // where the next k-step's fragments are
     const int rslot_a = PAR == 0 ? acur : acur ^ 1;
@@ -481,7 +487,7 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
       if (i < 8) fw[NPAR][i] = read_w(NPAR, i, rslot_w);
       else if (i < NREAD) fa_lo[i - 8] = read_a(NPAR, i - 8, rslot_a);
       else if (PAR == 0) issue_w1(wsrc, Dsrc, wslot2, i - NREAD, lds0, wave, lane);
-      else issue_a1(asrc, over ? nxt.offA[i - NREAD] : cur.offA[i - NREAD], Dsrc, acur, i - NREAD, lds0, wave);
+      else issue_a1(over ? nxt : cur, ln, Dsrc, acur, i - NREAD, lds0, wave);
 #pragma unroll
       for (int q = i * NM / NITEM; q < (i + 1) * NM / NITEM; ++q)
         mfma16_acc<false>(acc[q & 7][4 + (q >> 3)], fw[PAR][q & 7], fa_hi[q >> 3]);
@@ -533,13 +539,13 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
 // every variant executes the same loads and barriers; a wave row without live subtiles runs the
 // one-subtile variant on clamped rows and stores nothing
 template <bool GELU, class F>
-__device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, DmaRing& ring,
+__device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, const DmaLane& ln, DmaRing& ring,
                                              uint16_t* __restrict__ Cout, uint32_t lds0, int KD, int lane, int wave,
                                              int ldc, F&& before_epilogue) {
   const int wm = wave >> 1, wn = wave & 1;
   const int nsub = min(16, (cur.rows_left + 15) >> 4);  // live 16-row subtiles of this tile
   const int nj = __builtin_amdgcn_readfirstlane((nsub - wm + 1) >> 1);  // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
-#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ring, Cout, lds0, KD, wm, wn, lane, wave, ldc, before_epilogue)
+#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ln, ring, Cout, lds0, KD, wm, wn, lane, wave, ldc, before_epilogue)
   switch (nj) {
     case 8: LOCMOE_DMA_TILE(8); break;
     case 7: LOCMOE_DMA_TILE(7); break;
@@ -572,11 +578,12 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   if (mt * kBM >= rows) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const int KD = Kdim / (2 * kDmaBK);  // double steps
-  const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim, wave, lane);
+  const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim);
   const DmaTile nxt = tail_alias(cur, KD);
+  const DmaLane ln = make_lane(Kdim, wave, lane);
   DmaRing ring;
-  dma_prefill(cur, ring, lds0, wave, lane);
-  dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KD, lane, wave, Ndim, [] {});
+  dma_prefill(cur, ln, ring, lds0, wave, lane);
+  dma_tile_any<GELU>(cur, nxt, ln, ring, Cout, lds0, KD, lane, wave, Ndim, [] {});
   wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
 }
 
@@ -674,13 +681,14 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     const int within = jl - before;
     const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
     const int mtc = (rows + kBM - 1) / kBM;
-    return make_tile(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim, wave, lane);
+    return make_tile(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim);
   };
   int claimed = 0;
   if (dynamic && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);  // the tile after the first
   DmaTile cur = tile_at(lb);
+  const DmaLane ln = make_lane(Kdim, wave, lane);
   DmaRing ring;
-  dma_prefill(cur, ring, lds0, wave, lane);
+  dma_prefill(cur, ln, ring, lds0, wave, lane);
   for (;;) {
     // the claim goes from thread 0 to everybody through the one weight slot that is free between two tiles
     // (the tile's first k-step refills it: hence the second barrier)
@@ -692,7 +700,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     __syncthreads();
     const bool more = jn < total;
     const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KD);
-    dma_tile_any<GELU>(cur, nxt, ring, Cout, lds0, KD, lane, wave, Ndim, [&] {
+    dma_tile_any<GELU>(cur, nxt, ln, ring, Cout, lds0, KD, lane, wave, Ndim, [&] {
       if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
     });
     wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
