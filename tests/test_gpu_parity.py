@@ -283,6 +283,13 @@ def test_tuned_gemm_tiles_with_ragged_segments(env):
     run_full(env, wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4, dtype="bf16"), 300)
     # many segments for few tiles: empty segments, one- and two-tile segments in one persistent launch
     run_full(env, wl.small_config(T=6000, d=256, E=64, N=8, h=512, clusters=5), 300)
+    # the largest expert count of the persistent kernel (64 segments per XCD queue), mostly tiny or empty segments
+    run_full(env, wl.small_config(T=5000, d=512, E=512, N=8, h=256, clusters=6), 40)
+    # above it, and an expert count that is no multiple of 8: one tile per work-group
+    run_full(env, wl.small_config(T=3000, d=1024, E=1024, N=32, h=256, clusters=7), 8)
+    run_full(env, wl.small_config(T=2000, d=768, E=12, N=4, h=256, clusters=3), 400)
+    # the shortest K the packed layout allows (four double steps) with three m-tiles per segment
+    run_full(env, wl.small_config(T=3000, d=256, E=8, N=2, h=256, clusters=2), 700)
 
 
 def test_whole_path_bitwise_repeatable(env):
