@@ -287,8 +287,12 @@ extern "C" int locmoe_route(const locmoe_desc* desc, const float* g, const float
   if (!ws || ws_bytes < locmoe_workspace_bytes(desc)) return LOCMOE_ERR_WORKSPACE;
   hipStream_t s = as_stream(stream);
   const int E = desc->E;
+  // lanes per token: the whole expert axis up to 16 experts; beyond that, up to 128 experts, 16 lanes with
+  // several experts each (four tokens per wave side by side: the cross-lane reductions, which dominate the
+  // instruction count, shrink from six steps to four and are shared by four tokens); one wave per token above
   int S = 4;
-  while (S < E && S < 64) S *= 2;
+  while (S < E && S < 16) S *= 2;
+  if (E > 128) S = 64;
   const int G = kRouteThreads / S;
   const int step = G * kTokPerGroup;
   int tpb = ceil_div(desc->T, kRouteMaxBlocks);
@@ -298,10 +302,10 @@ extern "C" int locmoe_route(const locmoe_desc* desc, const float* g, const float
 #define LOCMOE_ROUTE(SS, EE) launch_route<SS, EE>(desc, g, eps, home, e2n, eid, w, ws, nb, tpb, s)
   if (S == 4) LOCMOE_ROUTE(4, 1);
   else if (S == 8) LOCMOE_ROUTE(8, 1);
-  else if (S == 16) LOCMOE_ROUTE(16, 1);
-  else if (S == 32) LOCMOE_ROUTE(32, 1);
-  else if (epl == 1) LOCMOE_ROUTE(64, 1);
-  else if (epl == 2) LOCMOE_ROUTE(64, 2);
+  else if (S == 16 && epl == 1) LOCMOE_ROUTE(16, 1);
+  else if (S == 16 && epl == 2) LOCMOE_ROUTE(16, 2);
+  else if (S == 16 && epl <= 4) LOCMOE_ROUTE(16, 4);
+  else if (S == 16) LOCMOE_ROUTE(16, 8);
   else if (epl <= 4) LOCMOE_ROUTE(64, 4);
   else if (epl <= 8) LOCMOE_ROUTE(64, 8);
   else LOCMOE_ROUTE(64, 16);
