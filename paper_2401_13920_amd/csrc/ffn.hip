@@ -342,11 +342,12 @@ __device__ __forceinline__ DmaLane make_lane(int Kdim, int wave, int lane) {
   return DmaLane{row0, (uint32_t)(((lane & 7) ^ ((row0 >> 1) & 7)) * 16), (uint32_t)Kdim * 2u};
 }
 
-__device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int mt,
-                                             int nt, int e, int Kdim, int Ndim) {
+// `span` = rows per m-tile of this segment (at most 256; the segment's last tile may hold fewer)
+__device__ __forceinline__ DmaTile make_tile(const uint16_t* A, const uint16_t* Wp, int seg0, int rows, int span,
+                                             int mt, int nt, int e, int Kdim, int Ndim) {
   DmaTile t;
-  const int m0 = mt * kBM;
-  t.rows_left = rows - m0;
+  const int m0 = mt * span;
+  t.rows_left = min(rows - m0, span);
   t.Abase = (const char*)(A + ((size_t)seg0 + m0) * Kdim);
   t.Wbase = (const char*)(Wp + ((size_t)e * Ndim + (size_t)nt * kBN) * (size_t)Kdim);
   t.crow0 = (size_t)seg0 + m0;
@@ -578,7 +579,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   if (mt * kBM >= rows) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const int KD = Kdim / (2 * kDmaBK);  // double steps
-  const DmaTile cur = make_tile(A, Wp, seg0, rows, mt, nt, buf_expert[r], Kdim, Ndim);
+  const DmaTile cur = make_tile(A, Wp, seg0, rows, kBM, mt, nt, buf_expert[r], Kdim, Ndim);
   const DmaTile nxt = tail_alias(cur, KD);
   const DmaLane ln = make_lane(Kdim, wave, lane);
   DmaRing ring;
@@ -680,8 +681,13 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     const int before = k ? __builtin_amdgcn_readfirstlane(__shfl(tab_cum, k - 1, 64)) : 0;
     const int within = jl - before;
     const int seg0 = seg_off[r], rows = seg_off[r + 1] - seg0;
+    // A segment's rows are spread evenly over its m-tiles (in whole 16-row subtiles): m-tiles of one weight
+    // tile that take equally long stay in step and share the weight stream through L2.  Cut at 256 rows, a
+    // short last tile ran ahead of its partner, the stream was fetched twice and the kernel became HBM-bound
+    // (272 rows per expert: 3.3 -> 2.45 ms for the second GEMM).
     const int mtc = (rows + kBM - 1) / kBM;
-    return make_tile(A, Wp, seg0, rows, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim);
+    const int span = ((rows + mtc - 1) / mtc + 15) & ~15;
+    return make_tile(A, Wp, seg0, rows, span, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim);
   };
   int claimed = 0;
   if (dynamic && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);  // the tile after the first
