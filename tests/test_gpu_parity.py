@@ -1,6 +1,6 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
 
-Bars (also in the design doc):
+Bars:
   * routing assignments, positions, slots, kept/segment/node offsets, row_token, dropped set and
     the send buffer rows: bit-exact, given the oracle's float32 gating values;
   * gating values: relative L2 <= 1e-5 and |diff| <= 1e-5 * (E/d) * sum_j |x_j| per element;
