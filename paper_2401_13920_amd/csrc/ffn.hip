@@ -295,7 +295,7 @@ typedef const char __attribute__((address_space(3))) * lds_cptr;
 __device__ __forceinline__ void dma_1k(const void* sbase, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase),
                "s"(lds_base)
-               : "memory");
+               : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
