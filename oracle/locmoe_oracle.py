@@ -13,6 +13,7 @@ Every function is a plain definition, in float64 unless stated:
 * locality loss         Eq. 6
 * capacity              Section 3.2.3: empirical capacity, Lemma 3, Theorem 1
 * expert FFN / combine  Eq. 1
+* token-to-gate angles  Section 3.2.3 (the assumption that defines delta_{i,j}), Section 4.1
 
 Readings where the paper is silent are spelled out at each function.  Every
 function here is pinned by the CPU tests against closed forms, brute force or
@@ -284,3 +285,50 @@ def moe_layer(x, home, e2n, E, N, C, weights, eps=None, relu=True, alpha=0.01, m
     out = expert_ffn(send, sl["seg_off"], sl["buf_expert"], weights)
     y = combine(out, sl["slot"], w)
     return dict(g=g, g32=g32, eid=eid, w=w, p=p, stats=stats, send=send, out=out, y=y, **sl)
+
+
+# --------------------------------------------------------------------------
+# Angles between tokens and gating weights (Section 3.2.3, Section 4.1)
+# --------------------------------------------------------------------------
+def token_gate_cosines(x: np.ndarray, E: int) -> np.ndarray:
+    """delta_{i,j} of Section 3.2.3: the cosine of the angle between token j and gating weight
+    omega_i (Eq. 4), as the plain normalised dot product, for every token and expert: [T, E].
+    A zero token has no angle; its cosines are set to 0."""
+    x = np.asarray(x, dtype=np.float64)
+    W = grap_weight(E, x.shape[1])
+    dots = x @ W.T
+    nx = np.sqrt(np.sum(x * x, axis=1))
+    nw = np.sqrt(np.sum(W * W, axis=1))
+    safe = np.where(nx > 0.0, nx, 1.0)
+    return np.where(nx[:, None] > 0.0, dots / (safe[:, None] * nw[None, :]), 0.0)
+
+
+def angle_stats(x: np.ndarray, eid: np.ndarray, E: int, shift: int, nbins: int):
+    """The measurement behind Section 4.1 ("Analysis for Expert Capacity"): for the tokens routed to
+    each expert i, the histogram of their cosine to omega_i and of their cosine to another expert
+    (expert (i + shift) mod E here), and the smallest cosine to omega_i among them.  The paper reads
+    its delta off such histograms; delta_hat below is the literal reading of the assumption in
+    Section 3.2.3 (every routed token satisfies delta_{i,j} >= delta): the smallest routed cosine.
+
+    Bins split [-1, 1] evenly; bin b = floor((c + 1) / 2 * nbins), clamped to [0, nbins - 1].
+    Returns c_self [T], c_other [T], hist_self [E, nbins], hist_other [E, nbins], cmin [E] (2.0 for an
+    expert without tokens: no cosine reaches it) and delta_hat (2.0 when there are no tokens)."""
+    cos = token_gate_cosines(x, E)
+    eid = np.asarray(eid, dtype=np.int64)
+    T = cos.shape[0]
+    rows = np.arange(T)
+    c_self = cos[rows, eid]
+    c_other = cos[rows, (eid + shift) % E]
+
+    def bins(c):
+        return np.clip(np.floor((c + 1.0) * 0.5 * nbins).astype(np.int64), 0, nbins - 1)
+
+    hist_self = np.zeros((E, nbins), dtype=np.int64)
+    hist_other = np.zeros((E, nbins), dtype=np.int64)
+    np.add.at(hist_self, (eid, bins(c_self)), 1)
+    np.add.at(hist_other, (eid, bins(c_other)), 1)
+    cmin = np.full(E, 2.0)
+    np.minimum.at(cmin, eid, c_self)
+    delta_hat = float(cmin.min()) if T > 0 else 2.0
+    return c_self, c_other, hist_self, hist_other, cmin, delta_hat
+

@@ -339,3 +339,84 @@ def test_workloads_are_seeded_and_representable():
     # bf16 rounding is round-to-nearest-even
     a = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7, -1.0 - 2 ** -8 - 2 ** -20], np.float32)
     assert wl.round_to_storage(a, "bf16").tolist() == [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7, -1.0 - 2 ** -7]
+
+
+# ------------------------------------------------------------------------------------------
+# Angles between tokens and gating weights (Section 3.2.3, Section 4.1)
+# ------------------------------------------------------------------------------------------
+def test_cosines_closed_forms():
+    E, d = 8, 64
+    # a constant token makes the same angle with every gating weight: cos = 1/sqrt(E)
+    c = orc.token_gate_cosines(np.full((1, d), -3.5), E)
+    assert np.allclose(c, -1.0 / math.sqrt(E), atol=1e-14)
+    # a token that lives on block i is parallel to omega_i and orthogonal to the others
+    x = np.zeros((E, d)); blk = d // E
+    for i in range(E):
+        x[i, i * blk:(i + 1) * blk] = 2.0 + i
+    assert np.allclose(orc.token_gate_cosines(x, E), np.eye(E), atol=1e-14)
+    # a zero token has no angle
+    assert np.all(orc.token_gate_cosines(np.zeros((2, d)), E) == 0.0)
+
+
+def test_cosines_are_the_coordinates_of_the_projection():
+    """The omega_i are orthogonal (Section 3.2.1), so the squared cosines of a token sum to the squared
+    length of its projection onto their span, relative to its own: at most 1, and exactly
+    E * mean_i(block mean^2) * (d/E) / |x|^2."""
+    rng = np.random.default_rng(3)
+    E, d = 16, 128
+    x = rng.normal(size=(200, d))
+    c = orc.token_gate_cosines(x, E)
+    s = np.sum(c * c, axis=1)
+    assert np.all(s <= 1.0 + 1e-12)
+    blockmeans = x.reshape(200, E, d // E).mean(axis=2)
+    assert np.allclose(s, (d // E) * np.sum(blockmeans ** 2, axis=1) / np.sum(x * x, axis=1), rtol=1e-12)
+    # and the cosine is the gating value up to the two norms: cos = g * sqrt(d/E) / |x|
+    g = orc.gate(x, E)
+    assert np.allclose(c, g * math.sqrt(d / E) / np.sqrt(np.sum(x * x, axis=1))[:, None], rtol=1e-12, atol=1e-15)
+
+
+def test_routed_cosine_is_the_largest_cosine():
+    """Lemma 1 (Appendix A.1): the routed expert is the one with the largest cosine, whenever some gating
+    value is positive."""
+    rng = np.random.default_rng(4)
+    E, d = 8, 64
+    x = rng.normal(size=(500, d))
+    g32 = orc.gate(x, E).astype(np.float32)
+    eid = orc.route(g32)[0]
+    c = orc.token_gate_cosines(x, E)
+    pos = g32.max(axis=1) > 0
+    c_self, _, _, _, _, _ = orc.angle_stats(x, eid, E, 1, 16)
+    assert np.allclose(c_self[pos], c.max(axis=1)[pos], rtol=0, atol=1e-7)   # (g32 rounding may swap near-ties)
+
+
+def test_cosine_tail_matches_lemma_3():
+    """Lemma 3: for tokens uniform on the sphere, the share with |cos| >= delta to a fixed direction is
+    p_delta.  The histogram of cosines to one gating weight must show that tail."""
+    rng = np.random.default_rng(5)
+    E, d, T = 4, 32, 200000
+    x = rng.normal(size=(T, d))                      # direction uniform on the sphere
+    c = orc.token_gate_cosines(x, E)[:, 2]
+    for delta in (0.1, 0.2, 0.35):
+        share = np.mean(np.abs(c) >= delta)
+        p = orc.p_delta(d, delta)
+        assert abs(share - p) < 4.0 * math.sqrt(p * (1 - p) / T) + 1e-4, (delta, share, p)
+
+
+def test_angle_stats_by_hand():
+    """Two experts, four tokens, checked against values worked out by hand."""
+    E, d = 2, 4
+    x = np.array([[1.0, 1.0, 0.0, 0.0],      # on block 0: cos 1 to omega_0, 0 to omega_1
+                  [0.0, 0.0, 3.0, 3.0],      # on block 1
+                  [1.0, 1.0, 1.0, 1.0],      # constant: 1/sqrt(2) to both
+                  [1.0, -1.0, 0.0, 0.0]])    # orthogonal to both
+    eid = np.array([0, 1, 1, 0])
+    c_self, c_other, hs, ho, cmin, dh = orc.angle_stats(x, eid, E, 1, 4)
+    r = 1.0 / math.sqrt(2.0)
+    assert np.allclose(c_self, [1.0, 1.0, r, 0.0]) and np.allclose(c_other, [0.0, 0.0, r, 0.0])
+    # bins of width 0.5 over [-1, 1]: 1.0 -> 3 (clamped), 0.707 -> 3, 0.0 -> 2
+    assert hs.tolist() == [[0, 0, 1, 1], [0, 0, 0, 2]]
+    assert ho.tolist() == [[0, 0, 2, 0], [0, 0, 1, 1]]
+    assert np.allclose(cmin, [0.0, r]) and dh == 0.0
+    # an expert without tokens keeps the sentinel; every token is counted once per histogram
+    _, _, hs3, ho3, cmin3, _ = orc.angle_stats(x, np.zeros(4, dtype=np.int64), 2, 1, 8)
+    assert cmin3[1] == 2.0 and hs3.sum() == 4 and ho3.sum() == 4 and hs3[1].sum() == 0
