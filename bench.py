@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the two grouped-GEMM kernels at the bench workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (KiB per dispatch; profiles/bench_config4_kernels_and_hbm_counters.txt).  FETCH_SIZE is scaled by 2.0,
 # the factor the same counter needs for a plain 1 GiB copy in the same run; WRITE_SIZE needs none.
-PMC_KIB = {"ffn_in": (4679370.0, 837589.1), "ffn_out": (4932219.7, 210171.4)}
+PMC_KIB = {"ffn_in": (4677365.9, 837588.9), "ffn_out": (4934791.6, 210171.6)}
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
@@ -180,6 +180,29 @@ def main() -> int:
         tf = flops / (ms[n] * 1e-3) / 1e12
         steps_detail[n] = {"ms": round(ms[n], 4), "TFLOP/s": round(tf, 1),
                            "mfma_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+    # the delta estimator of Section 4.1 (not part of the timed step): the gate pass that also writes the
+    # block sums of squares, and the cosine histograms / smallest routed cosine
+    nb = 64
+    xs, hs, b = sets[0]
+    q_dev = torch.empty_like(b.g)
+    hist = torch.empty(2, c.E, nb, dtype=torch.int32, device="cuda")
+    cmin = torch.empty(c.E, dtype=torch.float32, device="cuda")
+    dstat = torch.empty(4, dtype=torch.float32, device="cuda")
+    est = {"gate_sq": 0.0, "angle_stats": 0.0}
+    for k in range(reps):
+        xs, hs, b = sets[k % len(sets)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record(stream)
+        lm.locmoe_gate_sq(desc, xs, b.g, q_dev, stream); ev[1].record(stream)
+        lm.locmoe_angle_stats(desc, b.g, q_dev, b.eid, 1, nb, None, None, hist[0], hist[1], cmin, dstat, stream)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        est["gate_sq"] += ev[0].elapsed_time(ev[1]); est["angle_stats"] += ev[1].elapsed_time(ev[2])
+    est_bytes = {"gate_sq": c.T * c.d * s + 2 * c.T * c.E * 4, "angle_stats": 2 * c.T * c.E * 4 + 4 * c.T}
+    estimator = {"delta_hat": round(float(dstat[0]), 5), "nbins": nb}
+    for n in est:
+        t = est[n] / reps
+        estimator[n] = {"ms": round(t, 4), "GB/s": round(est_bytes[n] / (t * 1e-3) / 1e9, 1)}
     dom = "ffn_in" if ms["ffn_in"] >= ms["ffn_out"] else "ffn_out"
     achieved = flops / (ms[dom] * 1e-3) / 1e12
     kname = "ffn_gemm_dma_persistent" if desc.w_packed else "ffn_gemm_256"
@@ -201,6 +224,7 @@ def main() -> int:
         "dispatch_GBps": steps_detail["dispatch"]["GB/s"],
         "dispatch_hbm_frac": steps_detail["dispatch"]["hbm_frac"],
         "per_step": steps_detail,
+        "delta_estimator": estimator,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -102,6 +102,29 @@ int locmoe_route(const locmoe_desc* desc, const float* g, const float* eps, cons
                  const int32_t* e2n, int32_t* eid, float* w, int32_t* cnt, float* Psum,
                  float* stats, void* ws, size_t ws_bytes, void* stream);
 
+/* The gating value together with the block sums of squares, in the same pass over x:
+ *   g as in locmoe_gate;  q[m,i] = sum over block i of x[m,j]^2, so that |x_m|^2 = sum_i q[m,i].
+ *   With Eq. 4's weight (|omega_i| = sqrt(E/d)) the cosine between token m and gating weight i
+ *   (delta_{i,j} of Section 3.2.3) is g[m,i] * sqrt(d/E) / |x_m|.
+ *   x device [T,d] of x_dtype; g, q device [T,E] fp32 (written). */
+int locmoe_gate_sq(const locmoe_desc* desc, const void* x, float* g, float* q, void* stream);
+
+/* Angles between tokens and gating weights: the measurement of Section 4.1 ("Analysis for Expert
+ * Capacity") from which the paper reads its delta.  For token m routed to expert e = eid[m]:
+ *   c_self[m]  = cos(x_m, omega_e),  c_other[m] = cos(x_m, omega_{(e + shift) mod E})  (0 for a zero token);
+ *   hist_self[e][b], hist_other[e][b] count the tokens routed to e by bin b = floor((c + 1)/2 * nbins),
+ *   clamped to [0, nbins-1], of c_self resp. c_other;  cmin[e] = min c_self over the tokens routed to e
+ *   (2.0 for an expert without tokens);  stats[0] = delta_hat = min_e cmin[e], the literal reading of the
+ *   assumption in Section 3.2.3 (every routed token has delta_{i,j} >= delta); stats[1] = number of
+ *   experts with tokens; stats[2..3] = 0.
+ *   g, q device [T,E] fp32 from locmoe_gate_sq; eid device [T] i32 in [0,E); 1 <= nbins <= 65536;
+ *   c_self, c_other device [T] fp32 or NULL; hist_self, hist_other device [E*nbins] i32; cmin device [E]
+ *   fp32; stats device [4] fp32 (all written; no workspace).  Counts and minima only: independent of
+ *   the order in which tokens are processed. */
+int locmoe_angle_stats(const locmoe_desc* desc, const float* g, const float* q, const int32_t* eid,
+                       int32_t shift, int32_t nbins, float* c_self, float* c_other, int32_t* hist_self,
+                       int32_t* hist_other, float* cmin, float* stats, void* stream);
+
 /* Capacity-bounded stable dispatch (capacity: Section 3.2.3; layout: this library's).
  *   pos[m] = #{m' < m : eid[m'] = eid[m]}; token m is kept iff pos[m] < C (first come by token
  *   index).  Experts are laid out in buffer order = sorted by (e2n[e], e); rank r holds expert

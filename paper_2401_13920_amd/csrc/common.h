@@ -52,6 +52,18 @@ __device__ __forceinline__ float sum8_bf16(const uint4& v) {
 __device__ __forceinline__ float sum4_f32(const uint4& v) {
   return (__uint_as_float(v.x) + __uint_as_float(v.y)) + (__uint_as_float(v.z) + __uint_as_float(v.w));
 }
+// the same trees over the squares
+__device__ __forceinline__ float sumsq8_bf16(const uint4& v) {
+  float a0 = bf16_bits_to_f32(v.x & 0xFFFFu), a1 = __uint_as_float(v.x & 0xFFFF0000u);
+  float a2 = bf16_bits_to_f32(v.y & 0xFFFFu), a3 = __uint_as_float(v.y & 0xFFFF0000u);
+  float a4 = bf16_bits_to_f32(v.z & 0xFFFFu), a5 = __uint_as_float(v.z & 0xFFFF0000u);
+  float a6 = bf16_bits_to_f32(v.w & 0xFFFFu), a7 = __uint_as_float(v.w & 0xFFFF0000u);
+  return ((a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3)) + ((a4 * a4 + a5 * a5) + (a6 * a6 + a7 * a7));
+}
+__device__ __forceinline__ float sumsq4_f32(const uint4& v) {
+  const float a = __uint_as_float(v.x), b = __uint_as_float(v.y), c = __uint_as_float(v.z), d = __uint_as_float(v.w);
+  return (a * a + b * b) + (c * c + d * d);
+}
 
 // ---- cross-lane moves on the DPP path (no LDS traffic) ------------------------------------
 template <int CTRL>

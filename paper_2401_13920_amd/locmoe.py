@@ -20,7 +20,8 @@ LOCMOE_ERR_NULL, LOCMOE_ERR_SHAPE, LOCMOE_ERR_ARG, LOCMOE_ERR_WORKSPACE, LOCMOE_
 LOCMOE_F32, LOCMOE_BF16 = 0, 1
 
 EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "locmoe_capacity",
-           "locmoe_workspace_bytes", "locmoe_gate", "locmoe_route", "locmoe_dispatch",
+           "locmoe_workspace_bytes", "locmoe_gate", "locmoe_gate_sq", "locmoe_angle_stats", "locmoe_route",
+           "locmoe_dispatch",
            "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine",
            "locmoe_packed_weights_bytes", "locmoe_pack_weights")
 
@@ -64,6 +65,8 @@ def lib() -> C.CDLL:
     L.locmoe_workspace_bytes.restype = SZ
     L.locmoe_workspace_bytes.argtypes = [D]
     L.locmoe_gate.argtypes = [D, P, P, P]
+    L.locmoe_gate_sq.argtypes = [D, P, P, P, P]
+    L.locmoe_angle_stats.argtypes = [D, P, P, P, I32, I32] + [P] * 7
     L.locmoe_route.argtypes = [D] + [P] * 10 + [SZ, P]
     L.locmoe_dispatch.argtypes = [D] + [P] * 12 + [SZ, P]
     L.locmoe_expert_ffn.argtypes = [D] + [P] * 8
@@ -142,6 +145,17 @@ def locmoe_workspace_bytes(desc: locmoe_desc) -> int:
 # ---- device steps: same names and argument order as the C ABI --------------------------------
 def locmoe_gate(desc, x, g, stream=None):
     _check(lib().locmoe_gate(C.byref(desc), _ptr(x), _ptr(g), _stream(stream)))
+
+
+def locmoe_gate_sq(desc, x, g, q, stream=None):
+    _check(lib().locmoe_gate_sq(C.byref(desc), _ptr(x), _ptr(g), _ptr(q), _stream(stream)))
+
+
+def locmoe_angle_stats(desc, g, q, eid, shift, nbins, c_self, c_other, hist_self, hist_other, cmin, stats,
+                       stream=None):
+    _check(lib().locmoe_angle_stats(C.byref(desc), _ptr(g), _ptr(q), _ptr(eid), int(shift), int(nbins), _ptr(c_self),
+                                    _ptr(c_other), _ptr(hist_self), _ptr(hist_other), _ptr(cmin), _ptr(stats),
+                                    _stream(stream)))
 
 
 def locmoe_route(desc, g, eps, home, e2n, eid, w, cnt, Psum, stats, ws, ws_bytes, stream=None):

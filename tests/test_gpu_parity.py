@@ -6,7 +6,10 @@ Bars:
   * gating values: relative L2 <= 1e-5 and |diff| <= 1e-5 * (E/d) * sum_j |x_j| per element;
   * scores w, Psum and the loss scalars: 1e-5 relative;
   * FFN output and y: relative L2 <= 1e-2 against the float64 oracle (which rounds nothing; the
-    budget covers bf16 rounding of H, out and y).
+    budget covers bf16 rounding of H, out and y);
+  * cosines between tokens and gating weights, and their per-expert minimum: |diff| <= 1e-5; histogram
+    rows: totals exact, and every cumulative count between the oracle's for cosines moved by -1e-5 and
+    by +1e-5 (equal to the oracle's histogram wherever no cosine lies that close to a bin edge).
 """
 import sys
 import time
@@ -95,6 +98,62 @@ def check_dispatch(env, c, desc, b, x, x_dev, eid, e2n, C):
     send = hz.to_host_f32(b.send[:K])
     assert np.array_equal(send, x[s["row_token"]])                          # bit copies of the rows
     return s, K
+
+
+COS_TOL = 1e-5
+
+
+def check_angles(env, c, x, x_dev, desc, eid, shift, nbins, want_cos=True):
+    """locmoe_gate_sq + locmoe_angle_stats against the oracle's cosines, histograms and minima."""
+    torch, lm, hz = env
+    T, E = len(x), c.E
+    g_dev = torch.empty(T, E, dtype=torch.float32, device="cuda")
+    g2_dev = torch.empty_like(g_dev)
+    q_dev = torch.empty_like(g_dev)
+    lm.locmoe_gate(desc, x_dev, g_dev)
+    lm.locmoe_gate_sq(desc, x_dev, g2_dev, q_dev)
+    torch.cuda.synchronize()
+    assert torch.equal(g_dev, g2_dev)                       # the same gating arithmetic with or without q
+    blk = c.d // E
+    q_def = (x.astype(np.float64).reshape(T, E, blk) ** 2).sum(axis=2)
+    assert np.all(np.abs(q_dev.cpu().numpy() - q_def) <= 1e-5 * q_def + 1e-37)
+    cs_dev = torch.full((T,), 7.0, dtype=torch.float32, device="cuda") if want_cos else None
+    co_dev = torch.full((T,), 7.0, dtype=torch.float32, device="cuda") if want_cos else None
+    hs_dev = torch.full((E, nbins), -3, dtype=torch.int32, device="cuda")
+    ho_dev = torch.full((E, nbins), -3, dtype=torch.int32, device="cuda")
+    cmin_dev = torch.full((E,), -9.0, dtype=torch.float32, device="cuda")
+    st_dev = torch.full((4,), -9.0, dtype=torch.float32, device="cuda")
+    lm.locmoe_angle_stats(desc, g_dev, q_dev, i32(torch, eid), shift, nbins, cs_dev, co_dev, hs_dev, ho_dev,
+                          cmin_dev, st_dev)
+    torch.cuda.synchronize()
+    c_self, c_other, hist_self, hist_other, cmin, delta_hat = orc.angle_stats(x, eid, E, shift, nbins)
+    if want_cos:
+        assert np.all(np.abs(cs_dev.cpu().numpy() - c_self) <= COS_TOL)
+        assert np.all(np.abs(co_dev.cpu().numpy() - c_other) <= COS_TOL)
+
+    def cumulative(cv):
+        b = np.clip(np.floor((cv + 1.0) / 2.0 * nbins), 0, nbins - 1).astype(np.int64)
+        h = np.zeros((E, nbins), np.int64)
+        np.add.at(h, (np.asarray(eid, np.int64), b), 1)
+        return np.cumsum(h, axis=1)
+
+    for got_dev, ref_hist, cv in ((hs_dev, hist_self, c_self), (ho_dev, hist_other, c_other)):
+        got = got_dev.cpu().numpy().astype(np.int64)
+        assert got.min() >= 0
+        assert np.array_equal(got.sum(axis=1), np.bincount(eid, minlength=E))
+        cum = np.cumsum(got, axis=1)
+        # a cosine moved up by the tolerance lands in the same or a higher bin: fewer tokens at or below b
+        assert np.all(cumulative(cv + COS_TOL) <= cum) and np.all(cum <= cumulative(cv - COS_TOL))
+        scaled = (cv + 1.0) / 2.0 * nbins
+        if np.all(np.abs(scaled - np.round(scaled)) > COS_TOL * nbins):
+            assert np.array_equal(got, ref_hist)
+    got_min = cmin_dev.cpu().numpy()
+    empty = np.bincount(eid, minlength=E) == 0
+    assert np.all(got_min[empty] == 2.0) and np.all(cmin[empty] == 2.0)
+    assert np.all(np.abs(got_min[~empty] - cmin[~empty]) <= COS_TOL)
+    st = st_dev.cpu().numpy()
+    assert abs(st[0] - delta_hat) <= COS_TOL and st[1] == int((~empty).sum()) and st[2] == 0 and st[3] == 0
+    return delta_hat
 
 
 def packed_desc(lm, desc):
@@ -292,6 +351,34 @@ def test_tuned_gemm_tiles_with_ragged_segments(env):
     run_full(env, wl.small_config(T=3000, d=256, E=8, N=2, h=256, clusters=2), 700)
 
 
+def angles_case(env, c, shift, nbins, T=None, zero_rows=(), want_cos=True):
+    torch, lm, hz = env
+    x, _ = wl.hidden_states(c, T)
+    x = x.copy()
+    for m in zero_rows:
+        x[m] = 0.0                                            # a token without a direction
+    say(f"[angles] cfg={c.cfg} T={len(x)} d={c.d} E={c.E} dtype={c.dtype} shift={shift} nbins={nbins}")
+    desc = lm.make_desc(len(x), c.d, c.E, c.N, c.h, 1, c.dtype)
+    eid = orc.route(orc.gate(x, c.E).astype(np.float32))[0]
+    dh = check_angles(env, c, x, hz.to_device(x, c.dtype), desc, eid, shift, nbins, want_cos)
+    say(f"         delta_hat={dh:.5f}")
+
+
+def test_angles_between_tokens_and_gating_weights(env):
+    """Section 4.1's measurement (cosine histograms per expert, smallest routed cosine) on the paper-shaped
+    configurations and on every gate kernel variant."""
+    angles_case(env, wl.CONFIGS[1], 1, 64)
+    angles_case(env, wl.CONFIGS[2], 3, 100)
+    angles_case(env, wl.small_config(), 1, 7, zero_rows=(0, 50))
+    angles_case(env, wl.small_config(dtype="f32"), -1, 1)
+    angles_case(env, wl.small_config(T=5, E=1, N=1, d=8, h=8), 1, 4)                  # the other expert is itself
+    angles_case(env, wl.small_config(T=2500, d=5120, E=128, N=16, h=64, clusters=9), 64, 33, zero_rows=(2499,))
+    angles_case(env, wl.small_config(T=300, d=96, E=8, N=2, h=24), 9, 16)            # scalar gate path
+    angles_case(env, wl.small_config(T=300, d=96, E=8, N=2, h=24, dtype="f32"), 2, 16, want_cos=False)
+    angles_case(env, wl.small_config(T=700, d=1024, E=1024, N=32, h=8, clusters=7), 1, 8)
+    angles_case(env, wl.small_config(T=1111, d=1600, E=200, N=8, h=16, clusters=9), 199, 4096)
+
+
 def test_whole_path_bitwise_repeatable(env):
     """No atomics whose order could matter anywhere on the path: y is bit-identical from run to run, for the
     row-major and the packed-weight kernels."""
@@ -460,3 +547,8 @@ def test_config4_full_size_headline(env):
 def test_config5_full_size_routing_stress(env):
     c = wl.CONFIGS[5]
     run_big(env, c, c.C, with_ffn=False)
+
+
+def test_config4_full_size_angles(env):
+    """The headline shape: every token's cosine, the histograms and delta_hat against the oracle."""
+    angles_case(env, wl.CONFIGS[4], 1, 64)

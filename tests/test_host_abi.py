@@ -101,6 +101,12 @@ def test_descriptor_validation_without_gpu():
     assert _status(lm.locmoe_gate, dsc, p, p, 0) == lm.LOCMOE_ERR_SHAPE
     dsc = lm.make_desc(**good)
     assert _status(lm.locmoe_gate, dsc, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_gate_sq, dsc, p, p, None, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_gate_sq, lm.make_desc(**dict(good, d=60)), p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
+    assert _status(lm.locmoe_angle_stats, dsc, p, p, None, 1, 8, None, None, p, p, p, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_angle_stats, dsc, p, p, p, 1, 8, None, None, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_angle_stats, dsc, p, p, p, 1, 0, None, None, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
+    assert _status(lm.locmoe_angle_stats, dsc, p, p, p, 1, 1 << 20, None, None, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
     assert _status(lm.locmoe_route, dsc, p, None, None, None, p, p, p, p, p, None, 0, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_route, dsc, p, None, None, None, p, p, p, p, p, p, 16, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_route, dsc, p, None, None, None, None, p, p, p, p, p, 1 << 20, 0) == lm.LOCMOE_ERR_NULL
