@@ -184,6 +184,75 @@ int locmoe_expert_ffn_out(const locmoe_desc* desc, const void* H_ws, const int32
 int locmoe_combine(const locmoe_desc* desc, const void* out, const int32_t* slot, const float* w,
                    void* y, void* stream);
 
+/* ---- Backward of the same path -------------------------------------------------------------------
+ * What is differentiated is the training objective of Section 3.2.2 (the equation after Eq. 6),
+ * L_task = L_cross + L_aux + L_loc, as far as it depends on this layer: L_cross arrives as dy = dL_cross/dy,
+ * L_aux is Eq. 5 with f held fixed (a count has no gradient), L_loc is Eq. 6 differentiated through the mean
+ * router probability P in place of the assignment distribution (mu * KL(P || D_l)).  The argmax of Eq. 2 and
+ * the capacity drop carry no gradient; ReLU'(0) = 0; the GrAP weight of Eq. 4 is not trainable, so the
+ * gradients are dx, dW_in and dW_out.  Order of calls: combine_bwd, the expert FFN backward, route_bwd,
+ * dispatch_bwd.  Same descriptor, dtypes, stream and error behaviour as the forward entry points. */
+
+/* Eq. 1 under top-1 (y_m = w_m out[slot_m]), backward:
+ *   dout[slot[m],:] = w[m] * dy[m,:]  (rounded to x_dtype)  and  dw[m] = <dy[m,:], out[slot[m],:]>  (fp32)
+ *   for a kept token; dw[m] = 0 for a dropped one, whose dy row is not read.
+ *   dy device [T,d], out device [E*C,d], dout device [E*C,d] (rows [0,K) written) of x_dtype;
+ *   slot device [T] i32; w, dw device [T] fp32. */
+int locmoe_combine_bwd(const locmoe_desc* desc, const void* dy, const void* out, const int32_t* slot,
+                       const float* w, void* dout, float* dw, void* stream);
+
+/* Eq. 3, the ReLU below it and the two batch losses, backward.  With s = g + eps, G = ReLU(s) (or s if
+ * desc->relu == 0), p = softmax(G) recomputed as the forward did:
+ *   coef[i] = alpha n f_i / T  (Eq. 5, f_i = cnt[i]/T fixed)  +  mu (ln(P_i / D_l[i]) + 1) / T  (Eq. 6 through
+ *             P_i = Psum[i]/T; only if home != NULL and mu != 0; D_l as in locmoe_route);
+ *   dp[m,i] = [i = eid[m]] dw[m] + coef[i];   dG = p * (dp - <p, dp>);   dg[m,i] = dG[m,i] where s > 0 (ReLU).
+ *   g device [T,E] fp32; eps device [E] or NULL; home device [T] or NULL; e2n device [E] or NULL (as in
+ *   locmoe_route); eid device [T]; cnt device [E] i32 and Psum device [E] fp32 from locmoe_route; dw device [T];
+ *   coef device [E] fp32 (written); dg device [T,E] fp32 (written).  If some D_l[i] = 0 the forward KL is
+ *   infinite and the results are not finite. */
+int locmoe_route_bwd(const locmoe_desc* desc, const float* g, const float* eps, const int32_t* home,
+                     const int32_t* e2n, const int32_t* eid, const int32_t* cnt, const float* Psum,
+                     const float* dw, float* coef, float* dg, void* stream);
+
+/* Eq. 1's first linear map as locmoe_expert_ffn_in, and the pre-activation kept for the backward:
+ *   Z[r,:] = W_in[e] . send[r,:] (bf16),  H_ws[r,:] = GeLU of the same fp32 value (bf16).
+ *   Z device [E*C,h] bf16 (rows [0,K) written); everything else as locmoe_expert_ffn_in. */
+int locmoe_expert_ffn_in_save(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                              const int32_t* buf_expert, const void* W_in, void* H_ws, void* Z, void* stream);
+
+/* Transposed copies of the expert weights, which the data gradients contract with (row-major, bf16):
+ *   W_in_t[e] = W_in[e]^T  [d,h],   W_out_t[e] = W_out[e]^T  [h,d].
+ *   All four device [E,h*d]; not the packed layout (to use the packed kernels for the backward, pack the
+ *   transposes: locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_t_packed, W_in_t_packed), W_out_t having the
+ *   shape of W_in and W_in_t that of W_out). */
+int locmoe_transpose_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_t,
+                             void* W_out_t, void* stream);
+
+/* Eq. 1, backward with respect to the rows (data gradients), two grouped GEMMs like the forward:
+ *   dZ[r,:]    = (W_out[e]^T . dout[r,:]) * GeLU'(Z[r,:])   (bf16; GeLU'(v) = Phi(v) + v phi(v))
+ *   dsend[r,:] = W_in[e]^T . dZ[r,:]                        (x_dtype)
+ *   dout device [E*C,d] x_dtype (rows [0,K) read); Z device [E*C,h] bf16 from locmoe_expert_ffn_in_save;
+ *   W_out_t, W_in_t: the transposed weights, row-major or packed as desc->w_packed says (see above);
+ *   dZ device [E*C,h] bf16 and dsend device [E*C,d] x_dtype (rows [0,K) written). */
+int locmoe_expert_ffn_dgrad(const locmoe_desc* desc, const void* dout, const void* Z, const int32_t* seg_off,
+                            const int32_t* buf_expert, const void* W_out_t, const void* W_in_t, void* dZ,
+                            void* dsend, void* stream);
+
+/* Eq. 1, backward with respect to the weights, summed over each expert's rows of the send buffer:
+ *   dW_in[e]  = sum_r dZ[r,:] (x) send[r,:]   [h,d],     dW_out[e] = sum_r dout[r,:] (x) H[r,:]   [d,h]
+ *   (fp32 accumulation, rounded once to bf16; zeros for an expert without rows: every element is written).
+ *   send, dout device [E*C,d] x_dtype; H, dZ device [E*C,h] bf16; dW_in, dW_out device [E,h*d] bf16,
+ *   row-major in Eq. 1's orientation whatever desc->w_packed says. */
+int locmoe_expert_ffn_wgrad(const locmoe_desc* desc, const void* send, const void* H, const void* dout,
+                            const void* dZ, const int32_t* seg_off, const int32_t* buf_expert, void* dW_in,
+                            void* dW_out, void* stream);
+
+/* The dispatch permutation and Eq. 4, backward, in one pass over dx:
+ *   dx[m,j] = (slot[m] >= 0 ? dsend[slot[m],j] : 0) + (E/d) * dg[m, j / (d/E)]   (fp32 sum, rounded to x_dtype)
+ *   dsend device [E*C,d] and dx device [T,d] of x_dtype (every dx row written); slot device [T]; dg device [T,E]. */
+int locmoe_dispatch_bwd(const locmoe_desc* desc, const void* dsend, const int32_t* slot, const float* dg,
+                        void* dx, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

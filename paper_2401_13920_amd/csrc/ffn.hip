@@ -47,12 +47,41 @@ __device__ __forceinline__ f32x16 mfma_bf16(const bf16x8& a, const bf16x8& b, co
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// GeLU'(v) = Phi(v) + v phi(v) for factors of outputs that are rounded to bf16, from the same polynomial:
+// Phi(-|v|) = exp2(q(|v|)) / 2 (absolute error below 2.3e-5), phi(v) = exp2(-v^2 log2(e)/2) / sqrt(2 pi).
+__device__ __forceinline__ float gelu_grad_bf16(float v) {
+  const float x = fminf(fabsf(v), kGeluXMax);
+  float q = kGeluCoef[kGeluDegree];
+#pragma unroll
+  for (int k = kGeluDegree - 1; k >= 0; --k) q = fmaf(q, x, kGeluCoef[k]);
+  const float tail = 0.5f * __builtin_amdgcn_exp2f(q);  // Phi(-|v|)
+  const float Phi = v >= 0.f ? 1.0f - tail : tail;
+  const float phi = 0.3989422804f * __builtin_amdgcn_exp2f(-0.7213475204f * v * v);
+  return fmaf(v, phi, Phi);
+}
+
+// What happens to an accumulator on its way to memory
+constexpr int kEpiNone = 0;      // rounded and stored
+constexpr int kEpiGelu = 1;      // GeLU, then rounded and stored (H of Eq. 1)
+constexpr int kEpiGeluSave = 2;  // the same, and the pre-activation Z is stored (bf16) to `aux` for the backward
+constexpr int kEpiGeluGrad = 3;  // multiplied by GeLU'(Z), Z read from `aux` (bf16): dZ = dH * GeLU'(Z)
+
 // One accumulator quad -> memory.  q holds D[n0..n0+3][m] for one row m.
-template <bool GELU, bool OUT_F32>
-__device__ __forceinline__ void store_quad(void* C, size_t row, int ldc, int n0, float q0, float q1, float q2,
-                                           float q3) {
-  static_assert(!(GELU && OUT_F32), "the hidden activations H are always stored as bf16");
-  if (GELU) { q0 = gelu_bf16(q0); q1 = gelu_bf16(q1); q2 = gelu_bf16(q2); q3 = gelu_bf16(q3); }
+template <int EPI, bool OUT_F32>
+__device__ __forceinline__ void store_quad(void* C, uint16_t* aux, size_t row, int ldc, int n0, float q0, float q1,
+                                           float q2, float q3) {
+  static_assert(!(EPI != kEpiNone && OUT_F32), "the hidden activations and their gradients are stored as bf16");
+  if (EPI == kEpiGeluSave) *(uint2*)(aux + row * ldc + n0) = make_uint2(pack_bf16x2(q0, q1), pack_bf16x2(q2, q3));
+  if (EPI == kEpiGelu || EPI == kEpiGeluSave) {
+    q0 = gelu_bf16(q0); q1 = gelu_bf16(q1); q2 = gelu_bf16(q2); q3 = gelu_bf16(q3);
+  }
+  if (EPI == kEpiGeluGrad) {
+    const uint2 z = *(const uint2*)(aux + row * ldc + n0);
+    q0 *= gelu_grad_bf16(bf16_bits_to_f32(z.x & 0xFFFFu));
+    q1 *= gelu_grad_bf16(__uint_as_float(z.x & 0xFFFF0000u));
+    q2 *= gelu_grad_bf16(bf16_bits_to_f32(z.y & 0xFFFFu));
+    q3 *= gelu_grad_bf16(__uint_as_float(z.y & 0xFFFF0000u));
+  }
   if (OUT_F32) {
     *(float4*)((float*)C + row * ldc + n0) = make_float4(q0, q1, q2, q3);
   } else {
@@ -67,10 +96,10 @@ __device__ __forceinline__ void store_quad(void* C, size_t row, int ldc, int n0,
 constexpr int kGenThreads = 256;
 constexpr int kGenLd = 40;  // LDS row stride in bf16 elements (32 + 8 pad), 80 bytes
 
-template <bool A_F32, bool GELU, bool OUT_F32>
+template <bool A_F32, int EPI, bool OUT_F32>
 __global__ __launch_bounds__(kGenThreads) void ffn_gemm_generic(const void* __restrict__ A,
                                                                 const uint16_t* __restrict__ W,
-                                                                void* __restrict__ Cout,
+                                                                void* __restrict__ Cout, uint16_t* aux,
                                                                 const int32_t* __restrict__ seg_off,
                                                                 const int32_t* __restrict__ buf_expert, int Kdim,
                                                                 int Ndim, int MT) {
@@ -120,7 +149,7 @@ __global__ __launch_bounds__(kGenThreads) void ffn_gemm_generic(const void* __re
     for (int vq = 0; vq < 4; ++vq) {
       const int n = n0 + wn * 32 + vq * 8 + (lane >> 5) * 4;
       if (n < Ndim)  // Ndim % 8 == 0 and n % 4 == 0: the quad is entirely inside or outside
-        store_quad<GELU, OUT_F32>(Cout, (size_t)seg0 + m, Ndim, n, acc[vq * 4 + 0], acc[vq * 4 + 1],
+        store_quad<EPI, OUT_F32>(Cout, aux, (size_t)seg0 + m, Ndim, n, acc[vq * 4 + 0], acc[vq * 4 + 1],
                                   acc[vq * 4 + 2], acc[vq * 4 + 3]);
     }
   }
@@ -141,10 +170,10 @@ constexpr int kFastSmem = 2 * kStageBytes;
 template <int SH>
 __device__ __forceinline__ int swz(int row, int chunk) { return (chunk ^ ((row >> SH) & 7)) << 4; }
 
-template <bool GELU, bool OUT_F32, int SH>
+template <int EPI, bool OUT_F32, int SH>
 __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __restrict__ A,
                                                              const uint16_t* __restrict__ W,
-                                                             void* __restrict__ Cout,
+                                                             void* __restrict__ Cout, uint16_t* aux,
                                                              const int32_t* __restrict__ seg_off,
                                                              const int32_t* __restrict__ buf_expert, int Kdim,
                                                              int Ndim, int MT, int NT, int total) {
@@ -241,7 +270,7 @@ __global__ __launch_bounds__(kFastThreads) void ffn_gemm_256(const uint16_t* __r
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
           const int n = nt * kBN + wn * 64 + ni * 32 + vq * 8 + khalf * 4;
-          store_quad<GELU, OUT_F32>(Cout, (size_t)seg0 + m, Ndim, n, acc[ni][mi][vq * 4 + 0],
+          store_quad<EPI, OUT_F32>(Cout, aux, (size_t)seg0 + m, Ndim, n, acc[ni][mi][vq * 4 + 0],
                                     acc[ni][mi][vq * 4 + 1], acc[ni][mi][vq * 4 + 2], acc[ni][mi][vq * 4 + 3]);
         }
     }
@@ -407,9 +436,9 @@ __device__ __forceinline__ void dma_prefill(const DmaTile& t, const DmaLane& ln,
 // loop's prefetches run on into `nxt`, so on exit the same holds for `nxt`, and this tile's stores may
 // still be in flight: the caller drains everything with vmcnt(0) before the next tile (stores and
 // direct-to-LDS loads do not retire in order relative to each other, so no smaller count is safe there).
-template <int NJ, bool GELU, class F>
+template <int NJ, int EPI, class F>
 __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt, const DmaLane& ln, DmaRing& ring,
-                                         uint16_t* __restrict__ Cout, uint32_t lds0, int KD, int wm, int wn,
+                                         uint16_t* __restrict__ Cout, uint16_t* aux, uint32_t lds0, int KD, int wm, int wn,
                                          int lane, int wave, int ldc, F&& before_epilogue) {
   // NJ = live 16-row activation subtiles of this wave
   constexpr int NLO = NJ < 4 ? NJ : 4;        // first group of subtiles
@@ -531,7 +560,7 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
 #pragma unroll
       for (int ni = 0; ni < 8; ++ni) {
         const int n = cur.n_base + wn * 128 + ni * 16 + kqe * 4;  // a lane holds rows 4*(l/16)..+3 of the 16x16 tile D[n][m]
-        store_quad<GELU, false>(Cout, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
+        store_quad<EPI, false>(Cout, aux, cur.crow0 + m, ldc, n, acc[ni][j][0], acc[ni][j][1], acc[ni][j][2], acc[ni][j][3]);
       }
     }
   }
@@ -539,14 +568,14 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
 
 // every variant executes the same loads and barriers; a wave row without live subtiles runs the
 // one-subtile variant on clamped rows and stores nothing
-template <bool GELU, class F>
+template <int EPI, class F>
 __device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& nxt, const DmaLane& ln, DmaRing& ring,
-                                             uint16_t* __restrict__ Cout, uint32_t lds0, int KD, int lane, int wave,
+                                             uint16_t* __restrict__ Cout, uint16_t* aux, uint32_t lds0, int KD, int lane, int wave,
                                              int ldc, F&& before_epilogue) {
   const int wm = wave >> 1, wn = wave & 1;
   const int nsub = min(16, (cur.rows_left + 15) >> 4);  // live 16-row subtiles of this tile
   const int nj = __builtin_amdgcn_readfirstlane((nsub - wm + 1) >> 1);  // ... of which this wave row owns nj (subtiles wm, wm+2, ...)
-#define LOCMOE_DMA_TILE(N) dma_tile<N, GELU>(cur, nxt, ln, ring, Cout, lds0, KD, wm, wn, lane, wave, ldc, before_epilogue)
+#define LOCMOE_DMA_TILE(N) dma_tile<N, EPI>(cur, nxt, ln, ring, Cout, aux, lds0, KD, wm, wn, lane, wave, ldc, before_epilogue)
   switch (nj) {
     case 8: LOCMOE_DMA_TILE(8); break;
     case 7: LOCMOE_DMA_TILE(7); break;
@@ -562,10 +591,10 @@ __device__ __forceinline__ void dma_tile_any(const DmaTile& cur, const DmaTile& 
 
 // One tile per work-group, segments in buffer order: the shape of the grid for expert counts that the
 // persistent kernel below does not take.
-template <bool GELU>
+template <int EPI>
 __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __restrict__ A,
                                                             const uint16_t* __restrict__ Wp,
-                                                            uint16_t* __restrict__ Cout,
+                                                            uint16_t* __restrict__ Cout, uint16_t* aux,
                                                             const int32_t* __restrict__ seg_off,
                                                             const int32_t* __restrict__ buf_expert, int Kdim,
                                                             int Ndim, int MT, int NT) {
@@ -584,7 +613,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   const DmaLane ln = make_lane(Kdim, wave, lane);
   DmaRing ring;
   dma_prefill(cur, ln, ring, lds0, wave, lane);
-  dma_tile_any<GELU>(cur, nxt, ln, ring, Cout, lds0, KD, lane, wave, Ndim, [] {});
+  dma_tile_any<EPI>(cur, nxt, ln, ring, Cout, aux, lds0, KD, lane, wave, Ndim, [] {});
   wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
 }
 
@@ -622,10 +651,10 @@ __device__ __forceinline__ void leave_queues(unsigned int* queue, unsigned group
 // segment list in two registers (lane k: segment of local rank k and the inclusive tile count up to it;
 // E/8 <= 64), built once in LDS before the pipeline starts.  The claimed index reaches the other waves
 // through the one weight slot that is free between two tiles.
-template <bool GELU>
+template <int EPI>
 __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uint16_t* __restrict__ A,
                                                                        const uint16_t* __restrict__ Wp,
-                                                                       uint16_t* __restrict__ Cout,
+                                                                       uint16_t* __restrict__ Cout, uint16_t* aux,
                                                                        const int32_t* __restrict__ seg_off,
                                                                        const int32_t* __restrict__ buf_expert,
                                                                        int Kdim, int Ndim, int NT, int E,
@@ -706,7 +735,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     __syncthreads();
     const bool more = jn < total;
     const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KD);
-    dma_tile_any<GELU>(cur, nxt, ln, ring, Cout, lds0, KD, lane, wave, Ndim, [&] {
+    dma_tile_any<EPI>(cur, nxt, ln, ring, Cout, aux, lds0, KD, lane, wave, Ndim, [&] {
       if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
     });
     wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
@@ -752,29 +781,59 @@ inline unsigned next_launch_id() {
   return launches.fetch_add(1u) + 1u;
 }
 
-template <bool GELU>
-int launch_dma(const void* A, const void* Wp, void* C, const int32_t* seg_off, const int32_t* buf_expert, int E,
+template <int EPI>
+int launch_dma(const void* A, const void* Wp, void* C, void* aux, const int32_t* seg_off, const int32_t* buf_expert, int E,
                int rows_max, int Kdim, int Ndim, hipStream_t st) {
   const int MT = ceil_div(rows_max, kBM), NT = Ndim / kBN;
   const long long total = (long long)E * MT * NT;
   if (total > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
   if (E % 8 == 0 && E <= 512) {
-    auto kern = ffn_gemm_dma_persistent<GELU>;
+    auto kern = ffn_gemm_dma_persistent<EPI>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
       return LOCMOE_ERR_HIP;
     // one work-group per compute unit (160 KiB of LDS each), a multiple of 8 so that every XCD gets as many
     const long long groups = std::min<long long>((cu_count() / 8) * 8, (total + 7) / 8 * 8);
     const unsigned launch_id = next_launch_id();
     hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
-                       (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, NT, E, launch_id);
+                       (const uint16_t*)Wp, (uint16_t*)C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, NT, E, launch_id);
     return launch_status();
   }
-  auto kern = ffn_gemm_dma<GELU>;
+  auto kern = ffn_gemm_dma<EPI>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
     return LOCMOE_ERR_HIP;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
-                     (const uint16_t*)Wp, (uint16_t*)C, seg_off, buf_expert, Kdim, Ndim, MT, NT);
+                     (const uint16_t*)Wp, (uint16_t*)C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, MT, NT);
   return launch_status();
+}
+
+// out[z][c][r] = in[z][r][c] for bf16 matrices whose sides are multiples of 8: 64x64 tiles through LDS,
+// 16-byte global accesses on both sides.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in,
+                                                             uint16_t* __restrict__ out, int R, int Cc) {
+  __shared__ uint16_t tile[64][66];  // 33 words per row: the column reads below fall into distinct banks
+  const size_t base = (size_t)blockIdx.z * R * Cc;
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int t = threadIdx.x, ch = t & 7;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int row = (t >> 3) + 32 * k;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + row < R && c0 + ch * 8 < Cc) v = *(const uint4*)(in + base + (size_t)(r0 + row) * Cc + c0 + ch * 8);
+    uint32_t* dst = (uint32_t*)&tile[row][ch * 8];
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int col = (t >> 3) + 32 * k;  // a column of the input tile = a row of the output
+    if (c0 + col < Cc && r0 + ch * 8 < R) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        w[i] = (uint32_t)tile[ch * 8 + 2 * i][col] | ((uint32_t)tile[ch * 8 + 2 * i + 1][col] << 16);
+      *(uint4*)(out + base + (size_t)(c0 + col) * R + r0 + ch * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
 }
 
 // shapes the packed layout and the DMA kernel support
@@ -783,27 +842,68 @@ inline bool packable(const locmoe_desc* p) {
          (long long)p->h * 2 * 256 < 0x7FFFFFFFLL;
 }
 
-template <bool A_F32, bool GELU, bool OUT_F32>
-int launch_gemm(const void* A, const void* W, void* C, const int32_t* seg_off, const int32_t* buf_expert, int E,
+template <bool A_F32, int EPI, bool OUT_F32>
+int launch_gemm(const void* A, const void* W, void* C, void* aux, const int32_t* seg_off, const int32_t* buf_expert, int E,
                 int rows_max, int Kdim, int Ndim, hipStream_t st) {
   if (!A_F32 && Kdim % kBK == 0 && Ndim % kBN == 0) {
     const int MT = ceil_div(rows_max, kBM), NT = Ndim / kBN;
     const long long total = (long long)E * MT * NT;
     if (total <= 0x7FFFFFFFLL) {
-      auto kern = ffn_gemm_256<GELU, OUT_F32, 1>;
+      auto kern = ffn_gemm_256<EPI, OUT_F32, 1>;
       if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kFastSmem) !=
           hipSuccess)
         return LOCMOE_ERR_HIP;
       hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kFastThreads), kFastSmem, st, (const uint16_t*)A,
-                         (const uint16_t*)W, C, seg_off, buf_expert, Kdim, Ndim, MT, NT, (int)total);
+                         (const uint16_t*)W, C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, MT, NT, (int)total);
       return launch_status();
     }
   }
   const int MT = ceil_div(rows_max, 64);
   if ((long long)E * MT > 65535) return LOCMOE_ERR_SHAPE;
-  hipLaunchKernelGGL((ffn_gemm_generic<A_F32, GELU, OUT_F32>), dim3(ceil_div(Ndim, 64), E * MT),
-                     dim3(kGenThreads), 0, st, A, (const uint16_t*)W, C, seg_off, buf_expert, Kdim, Ndim, MT);
+  hipLaunchKernelGGL((ffn_gemm_generic<A_F32, EPI, OUT_F32>), dim3(ceil_div(Ndim, 64), E * MT),
+                     dim3(kGenThreads), 0, st, A, (const uint16_t*)W, C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, MT);
   return launch_status();
+}
+
+}  // namespace
+}  // namespace locmoe
+
+namespace locmoe {
+namespace {
+
+// C[rows, h] = epilogue(A[rows, d] . W[h, d]^T): the first GEMM of Eq. 1 and, with the transposed W_out in
+// place of W_in, the first GEMM of its backward
+template <int EPI>
+int gemm_d_to_h(const locmoe_desc* desc, const void* A, const int32_t* seg_off, const int32_t* buf_expert,
+                const void* W, void* Cbf16, void* aux, void* stream) {
+  const int rows_max = desc->C < desc->T ? desc->C : desc->T;  // kept[e] <= min(C, T)
+  if (desc->w_packed) {
+    if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
+    return launch_dma<EPI>(A, W, Cbf16, aux, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h,
+                           as_stream(stream));
+  }
+  if (desc->x_dtype == LOCMOE_F32)
+    return launch_gemm<true, EPI, false>(A, W, Cbf16, aux, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h,
+                                         as_stream(stream));
+  return launch_gemm<false, EPI, false>(A, W, Cbf16, aux, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h,
+                                        as_stream(stream));
+}
+
+// C[rows, d] = A[rows, h] . W[d, h]^T, A bf16, C of the storage type: the second GEMM of Eq. 1 and, with the
+// transposed W_in in place of W_out, the second GEMM of its backward
+int gemm_h_to_d(const locmoe_desc* desc, const void* A, const int32_t* seg_off, const int32_t* buf_expert,
+                const void* W, void* C, void* stream) {
+  const int rows_max = desc->C < desc->T ? desc->C : desc->T;
+  if (desc->w_packed) {
+    if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
+    return launch_dma<kEpiNone>(A, W, C, nullptr, seg_off, buf_expert, desc->E, rows_max, desc->h, desc->d,
+                                as_stream(stream));
+  }
+  if (desc->x_dtype == LOCMOE_F32)
+    return launch_gemm<false, kEpiNone, true>(A, W, C, nullptr, seg_off, buf_expert, desc->E, rows_max, desc->h,
+                                              desc->d, as_stream(stream));
+  return launch_gemm<false, kEpiNone, false>(A, W, C, nullptr, seg_off, buf_expert, desc->E, rows_max, desc->h,
+                                             desc->d, as_stream(stream));
 }
 
 }  // namespace
@@ -815,17 +915,17 @@ extern "C" int locmoe_expert_ffn_in(const locmoe_desc* desc, const void* send, c
   if (!desc || !send || !seg_off || !buf_expert || !W_in || !H_ws) return LOCMOE_ERR_NULL;
   const int st = check_desc(desc);
   if (st != LOCMOE_OK) return st;
-  const int rows_max = desc->C < desc->T ? desc->C : desc->T;  // kept[e] <= min(C, T)
-  if (desc->w_packed) {
-    if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
-    return launch_dma<true>(send, W_in, H_ws, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h,
-                            as_stream(stream));
-  }
-  if (desc->x_dtype == LOCMOE_F32)
-    return launch_gemm<true, true, false>(send, W_in, H_ws, seg_off, buf_expert, desc->E, rows_max, desc->d,
-                                          desc->h, as_stream(stream));
-  return launch_gemm<false, true, false>(send, W_in, H_ws, seg_off, buf_expert, desc->E, rows_max, desc->d,
-                                         desc->h, as_stream(stream));
+  return gemm_d_to_h<kEpiGelu>(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, stream);
+}
+
+extern "C" int locmoe_expert_ffn_in_save(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                                         const int32_t* buf_expert, const void* W_in, void* H_ws, void* Z,
+                                         void* stream) {
+  using namespace locmoe;
+  if (!desc || !send || !seg_off || !buf_expert || !W_in || !H_ws || !Z) return LOCMOE_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  return gemm_d_to_h<kEpiGeluSave>(desc, send, seg_off, buf_expert, W_in, H_ws, Z, stream);
 }
 
 extern "C" int locmoe_expert_ffn_out(const locmoe_desc* desc, const void* H_ws, const int32_t* seg_off,
@@ -834,17 +934,21 @@ extern "C" int locmoe_expert_ffn_out(const locmoe_desc* desc, const void* H_ws, 
   if (!desc || !H_ws || !seg_off || !buf_expert || !W_out || !out) return LOCMOE_ERR_NULL;
   const int st = check_desc(desc);
   if (st != LOCMOE_OK) return st;
-  const int rows_max = desc->C < desc->T ? desc->C : desc->T;
-  if (desc->w_packed) {
-    if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
-    return launch_dma<false>(H_ws, W_out, out, seg_off, buf_expert, desc->E, rows_max, desc->h, desc->d,
-                             as_stream(stream));
-  }
-  if (desc->x_dtype == LOCMOE_F32)
-    return launch_gemm<false, false, true>(H_ws, W_out, out, seg_off, buf_expert, desc->E, rows_max, desc->h,
-                                           desc->d, as_stream(stream));
-  return launch_gemm<false, false, false>(H_ws, W_out, out, seg_off, buf_expert, desc->E, rows_max, desc->h,
-                                          desc->d, as_stream(stream));
+  return gemm_h_to_d(desc, H_ws, seg_off, buf_expert, W_out, out, stream);
+}
+
+extern "C" int locmoe_expert_ffn_dgrad(const locmoe_desc* desc, const void* dout, const void* Z,
+                                       const int32_t* seg_off, const int32_t* buf_expert, const void* W_out_t,
+                                       const void* W_in_t, void* dZ, void* dsend, void* stream) {
+  using namespace locmoe;
+  if (!desc || !dout || !Z || !seg_off || !buf_expert || !W_out_t || !W_in_t || !dZ || !dsend) return LOCMOE_ERR_NULL;
+  int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  // dZ = (dout . W_out) * GeLU'(Z): W_out^T is [h,d], the orientation of W_in
+  st = gemm_d_to_h<kEpiGeluGrad>(desc, dout, seg_off, buf_expert, W_out_t, dZ, const_cast<void*>(Z), stream);
+  if (st != LOCMOE_OK) return st;
+  // dsend = dZ . W_in: W_in^T is [d,h], the orientation of W_out
+  return gemm_h_to_d(desc, dZ, seg_off, buf_expert, W_in_t, dsend, stream);
 }
 
 extern "C" int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
@@ -854,6 +958,23 @@ extern "C" int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, cons
   const int st = locmoe_expert_ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, stream);
   if (st != LOCMOE_OK) return st;
   return locmoe_expert_ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, stream);
+}
+
+extern "C" int locmoe_transpose_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_t,
+                                        void* W_out_t, void* stream) {
+  using namespace locmoe;
+  if (!desc || !W_in || !W_out || !W_in_t || !W_out_t) return LOCMOE_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  const int tiles_h = ceil_div(desc->h, 64), tiles_d = ceil_div(desc->d, 64);
+  if (tiles_h > 65535 || tiles_d > 65535 || desc->E > 65535) return LOCMOE_ERR_SHAPE;
+  hipStream_t s = as_stream(stream);
+  // W_in[e] is [h,d] -> [d,h];  W_out[e] is [d,h] -> [h,d]
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles_d, tiles_h, desc->E), dim3(256), 0, s, (const uint16_t*)W_in,
+                     (uint16_t*)W_in_t, desc->h, desc->d);
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles_h, tiles_d, desc->E), dim3(256), 0, s, (const uint16_t*)W_out,
+                     (uint16_t*)W_out_t, desc->d, desc->h);
+  return launch_status();
 }
 
 extern "C" size_t locmoe_packed_weights_bytes(const locmoe_desc* desc) {

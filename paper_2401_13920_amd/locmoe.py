@@ -23,7 +23,9 @@ EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "loc
            "locmoe_workspace_bytes", "locmoe_gate", "locmoe_gate_sq", "locmoe_angle_stats", "locmoe_route",
            "locmoe_dispatch",
            "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine",
-           "locmoe_packed_weights_bytes", "locmoe_pack_weights")
+           "locmoe_packed_weights_bytes", "locmoe_pack_weights", "locmoe_combine_bwd", "locmoe_route_bwd",
+           "locmoe_dispatch_bwd", "locmoe_expert_ffn_in_save", "locmoe_transpose_weights",
+           "locmoe_expert_ffn_dgrad", "locmoe_expert_ffn_wgrad")
 
 
 class locmoe_desc(C.Structure):
@@ -73,6 +75,13 @@ def lib() -> C.CDLL:
     L.locmoe_expert_ffn_in.argtypes = [D] + [P] * 6
     L.locmoe_expert_ffn_out.argtypes = [D] + [P] * 6
     L.locmoe_combine.argtypes = [D] + [P] * 5
+    L.locmoe_combine_bwd.argtypes = [D] + [P] * 7
+    L.locmoe_route_bwd.argtypes = [D] + [P] * 11
+    L.locmoe_dispatch_bwd.argtypes = [D] + [P] * 5
+    L.locmoe_expert_ffn_in_save.argtypes = [D] + [P] * 7
+    L.locmoe_transpose_weights.argtypes = [D] + [P] * 5
+    L.locmoe_expert_ffn_dgrad.argtypes = [D] + [P] * 9
+    L.locmoe_expert_ffn_wgrad.argtypes = [D] + [P] * 9
     L.locmoe_packed_weights_bytes.restype = SZ
     L.locmoe_packed_weights_bytes.argtypes = [D]
     L.locmoe_pack_weights.argtypes = [D] + [P] * 5
@@ -198,6 +207,40 @@ def locmoe_combine(desc, out, slot, w, y, stream=None):
     _check(lib().locmoe_combine(C.byref(desc), _ptr(out), _ptr(slot), _ptr(w), _ptr(y), _stream(stream)))
 
 
+def locmoe_combine_bwd(desc, dy, out, slot, w, dout, dw, stream=None):
+    _check(lib().locmoe_combine_bwd(C.byref(desc), _ptr(dy), _ptr(out), _ptr(slot), _ptr(w), _ptr(dout), _ptr(dw),
+                                    _stream(stream)))
+
+
+def locmoe_route_bwd(desc, g, eps, home, e2n, eid, cnt, Psum, dw, coef, dg, stream=None):
+    _check(lib().locmoe_route_bwd(C.byref(desc), _ptr(g), _ptr(eps), _ptr(home), _ptr(e2n), _ptr(eid), _ptr(cnt),
+                                  _ptr(Psum), _ptr(dw), _ptr(coef), _ptr(dg), _stream(stream)))
+
+
+def locmoe_dispatch_bwd(desc, dsend, slot, dg, dx, stream=None):
+    _check(lib().locmoe_dispatch_bwd(C.byref(desc), _ptr(dsend), _ptr(slot), _ptr(dg), _ptr(dx), _stream(stream)))
+
+
+def locmoe_expert_ffn_in_save(desc, send, seg_off, buf_expert, W_in, H_ws, Z, stream=None):
+    _check(lib().locmoe_expert_ffn_in_save(C.byref(desc), _ptr(send), _ptr(seg_off), _ptr(buf_expert), _ptr(W_in),
+                                           _ptr(H_ws), _ptr(Z), _stream(stream)))
+
+
+def locmoe_transpose_weights(desc, W_in, W_out, W_in_t, W_out_t, stream=None):
+    _check(lib().locmoe_transpose_weights(C.byref(desc), _ptr(W_in), _ptr(W_out), _ptr(W_in_t), _ptr(W_out_t),
+                                          _stream(stream)))
+
+
+def locmoe_expert_ffn_dgrad(desc, dout, Z, seg_off, buf_expert, W_out_t, W_in_t, dZ, dsend, stream=None):
+    _check(lib().locmoe_expert_ffn_dgrad(C.byref(desc), _ptr(dout), _ptr(Z), _ptr(seg_off), _ptr(buf_expert),
+                                         _ptr(W_out_t), _ptr(W_in_t), _ptr(dZ), _ptr(dsend), _stream(stream)))
+
+
+def locmoe_expert_ffn_wgrad(desc, send, H, dout, dZ, seg_off, buf_expert, dW_in, dW_out, stream=None):
+    _check(lib().locmoe_expert_ffn_wgrad(C.byref(desc), _ptr(send), _ptr(H), _ptr(dout), _ptr(dZ), _ptr(seg_off),
+                                         _ptr(buf_expert), _ptr(dW_in), _ptr(dW_out), _stream(stream)))
+
+
 # ---- buffer bundle: device allocations for one layer call (plumbing only) ---------------------
 @dataclass
 class Buffers:
@@ -250,3 +293,55 @@ def forward(desc, x, home, e2n, W_in, W_out, b: Buffers, eps=None, stream=None):
     locmoe_expert_ffn(desc, b.send, b.seg_off, b.buf_expert, W_in, W_out, b.H, b.out, stream)
     locmoe_combine(desc, b.out, b.slot, b.w, b.y, stream)
     return b.y
+
+
+# ---- training: forward that keeps what the backward needs, and the backward chain ------------------
+@dataclass
+class GradBuffers:
+    Z: object
+    dout: object
+    dw: object
+    dZ: object
+    dsend: object
+    coef: object
+    dg: object
+    dx: object
+    dW_in: object
+    dW_out: object
+
+
+def alloc_grad_buffers(desc: locmoe_desc, device="cuda") -> GradBuffers:
+    import torch
+    T, d, E, h, Cap = desc.T, desc.d, desc.E, desc.h, desc.C
+    xd = torch.bfloat16 if desc.x_dtype == LOCMOE_BF16 else torch.float32
+    rows = E * Cap
+    bf = dict(dtype=torch.bfloat16, device=device)
+    f32 = dict(dtype=torch.float32, device=device)
+    return GradBuffers(
+        Z=torch.empty(rows, h, **bf), dout=torch.empty(rows, d, dtype=xd, device=device), dw=torch.empty(T, **f32),
+        dZ=torch.empty(rows, h, **bf), dsend=torch.empty(rows, d, dtype=xd, device=device),
+        coef=torch.empty(E, **f32), dg=torch.empty(T, E, **f32), dx=torch.empty(T, d, dtype=xd, device=device),
+        dW_in=torch.empty(E, h, d, **bf), dW_out=torch.empty(E, d, h, **bf))
+
+
+def forward_train(desc, x, home, e2n, W_in, W_out, b: Buffers, gb: GradBuffers, eps=None, stream=None):
+    """The forward path with the pre-activation Z kept for the backward."""
+    locmoe_gate(desc, x, b.g, stream)
+    locmoe_route(desc, b.g, eps, home, e2n, b.eid, b.w, b.cnt, b.Psum, b.stats, b.ws, b.ws_bytes, stream)
+    locmoe_dispatch(desc, x, b.eid, e2n, b.pos, b.slot, b.kept, b.seg_off, b.node_off, b.buf_expert, b.row_token,
+                    b.send, b.ws, b.ws_bytes, stream)
+    locmoe_expert_ffn_in_save(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, gb.Z, stream)
+    locmoe_expert_ffn_out(desc, b.H, b.seg_off, b.buf_expert, W_out, b.out, stream)
+    locmoe_combine(desc, b.out, b.slot, b.w, b.y, stream)
+    return b.y
+
+
+def backward(desc, dy, home, e2n, W_in_t, W_out_t, b: Buffers, gb: GradBuffers, eps=None, stream=None):
+    """Enqueues the backward steps on one stream, in reverse order of the forward; W_in_t / W_out_t are the
+    transposed weights in the layout desc.w_packed names.  Leaves dx, dW_in, dW_out in gb."""
+    locmoe_combine_bwd(desc, dy, b.out, b.slot, b.w, gb.dout, gb.dw, stream)
+    locmoe_expert_ffn_dgrad(desc, gb.dout, gb.Z, b.seg_off, b.buf_expert, W_out_t, W_in_t, gb.dZ, gb.dsend, stream)
+    locmoe_expert_ffn_wgrad(desc, b.send, b.H, gb.dout, gb.dZ, b.seg_off, b.buf_expert, gb.dW_in, gb.dW_out, stream)
+    locmoe_route_bwd(desc, b.g, eps, home, e2n, b.eid, b.cnt, b.Psum, gb.dw, gb.coef, gb.dg, stream)
+    locmoe_dispatch_bwd(desc, gb.dsend, b.slot, gb.dg, gb.dx, stream)
+    return gb.dx

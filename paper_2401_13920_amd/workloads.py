@@ -149,6 +149,15 @@ def hidden_states(c: Config, T: int | None = None):
     return round_to_storage(x, c.dtype), home
 
 
+def upstream_grad(c: Config, T: int | None = None) -> np.ndarray:
+    """dL/dy [T, d] that the layers above would hand down: N(0, 1/d) per element (unit-norm rows on
+    average), float32 already rounded to the storage dtype."""
+    T = c.T if T is None else T
+    g = _rng(c.cfg, 7).standard_normal((T, c.d), dtype=np.float32)
+    g *= np.float32(1.0 / np.sqrt(c.d))
+    return round_to_storage(g, c.dtype)
+
+
 def expert_to_node(c: Config) -> np.ndarray:
     """Default placement: contiguous groups of E/N experts per node."""
     return (np.arange(c.E, dtype=np.int32) // (c.E // c.N)).astype(np.int32)

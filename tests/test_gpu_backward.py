@@ -1,0 +1,224 @@
+"""GPU parity of the backward path (through the C ABI) against the backward oracle, step by step on the
+oracle's own intermediates (rounded to what the step reads) and end to end on the GPU's.
+
+Bars:
+  * dout, dsend, dZ, dx, dW_in, dW_out (bf16 results of fp32 sums): relative L2 <= 1e-2 against the float64
+    oracle, as for the forward FFN; fp32 storage (dout, dsend, dx of an fp32 layer): 1e-2 as well where a
+    bf16 intermediate (Z, dZ, H) lies on the way, 1e-5 where none does;
+  * dw: |diff| <= 1e-5 * sum_j |dy_j out_j| (fp32 dot product in a fixed order);
+  * coef: 1e-5 relative;  dg: |diff| <= 2e-5 * max_i |dp[m,i]| per row (fp32 softmax, p <= 1);
+  * transposed weights: bit-exact;  experts without rows: dW exactly zero.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import locmoe_backward_oracle as bwd
+from oracle import locmoe_oracle as orc
+from paper_2401_13920_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2401_13920_amd import harness, locmoe as lm
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lm.lib()
+    return torch, lm, harness
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def i32(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def bf16_round(a):
+    return wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.asarray(a, np.float32)))
+
+
+def store_round(a, dtype):
+    return wl.round_to_storage(np.asarray(a, np.float32), dtype)
+
+
+def run_backward_case(env, c, C, *, T=None, eps=None, relu=True, e2n=None, use_home=True, alpha=0.3, mu=0.2):
+    torch, lm, hz = env
+    x, home = wl.hidden_states(c, T)
+    T = len(x)
+    dy = wl.upstream_grad(c, T)
+    if not use_home:
+        home = None
+    say(f"[bwd] cfg={c.cfg} T={T} d={c.d} E={c.E} N={c.N} h={c.h} C={C} dtype={c.dtype} relu={relu} "
+        f"eps={'y' if eps is not None else 'n'} home={'y' if use_home else 'n'}")
+    e2n_full = np.asarray(e2n if e2n is not None else np.arange(c.E) // (c.E // c.N))
+    ws = {e: wl.expert_weights(c, e) for e in range(c.E)}
+    ref = bwd.moe_layer_backward(x, home, e2n_full, c.E, c.N, C, lambda e: ws[e], dy, eps, relu, alpha, mu)
+    K = int(ref["seg_off"][-1])
+    desc = lm.make_desc(T, c.d, c.E, c.N, c.h, C, c.dtype, relu, alpha, mu)
+    b = lm.alloc_buffers(desc)
+    gb = lm.alloc_grad_buffers(desc)
+    x_dev, dy_dev = hz.to_device(x, c.dtype), hz.to_device(dy, c.dtype)
+    home_dev = None if home is None else i32(torch, home)
+    e2n_dev = None if e2n is None else i32(torch, e2n)
+    eps_dev = None if eps is None else torch.from_numpy(eps.astype(np.float32)).cuda()
+    W_in = torch.stack([hz.to_device(ws[e][0], "bf16") for e in range(c.E)])
+    W_out = torch.stack([hz.to_device(ws[e][1], "bf16") for e in range(c.E)])
+
+    # --- transposed weights: bit-exact
+    W_in_t, W_out_t = torch.empty_like(W_out), torch.empty_like(W_in)
+    lm.locmoe_transpose_weights(desc, W_in, W_out, W_in_t, W_out_t)
+    torch.cuda.synchronize()
+    assert torch.equal(W_in_t, W_in.transpose(1, 2).contiguous())
+    assert torch.equal(W_out_t, W_out.transpose(1, 2).contiguous())
+
+    slot_dev, seg_dev, be_dev = i32(torch, ref["slot"]), i32(torch, ref["seg_off"]), i32(torch, ref["buf_expert"])
+    rows = c.E * C
+
+    def rows_dev(a, dtype):
+        t = torch.zeros(rows, a.shape[1], dtype=hz.torch_dtype(dtype), device="cuda")
+        t[:K] = hz.to_device(a, dtype)
+        return t
+
+    # --- combine backward on the oracle's out and w
+    out_st = store_round(ref["out"], c.dtype)
+    w32 = ref["w"].astype(np.float32)
+    lm.locmoe_combine_bwd(desc, dy_dev, rows_dev(out_st, c.dtype), slot_dev, torch.from_numpy(w32).cuda(), gb.dout,
+                          gb.dw)
+    torch.cuda.synchronize()
+    dout_ref, dw_ref = bwd.combine_backward(dy, out_st, ref["slot"], w32)
+    assert rel_l2(hz.to_host_f32(gb.dout[:K]), dout_ref) <= (1e-2 if c.dtype == "bf16" else 1e-6)
+    kept = ref["slot"] >= 0
+    bound = np.zeros(T)
+    bound[kept] = np.abs(dy[kept].astype(np.float64) * out_st[ref["slot"][kept]]).sum(axis=1)
+    got_dw = gb.dw.cpu().numpy()
+    assert np.all(np.abs(got_dw - dw_ref) <= 1e-5 * bound + 1e-30)
+    assert np.all(got_dw[~kept] == 0.0)
+
+    # --- forward GEMM that keeps Z: H is what the plain entry point gives, Z the pre-activation
+    send_dev = rows_dev(ref["send"], c.dtype)
+    H_plain = torch.empty_like(b.H)
+    lm.locmoe_expert_ffn_in(desc, send_dev, seg_dev, be_dev, W_in, H_plain)
+    lm.locmoe_expert_ffn_in_save(desc, send_dev, seg_dev, be_dev, W_in, b.H, gb.Z)
+    torch.cuda.synchronize()
+    assert torch.equal(b.H[:K], H_plain[:K])
+    Z_ref = np.zeros((K, c.h))
+    for r, e in enumerate(ref["buf_expert"]):
+        a, z = int(ref["seg_off"][r]), int(ref["seg_off"][r + 1])
+        if z > a:
+            Z_ref[a:z] = ref["send"][a:z].astype(np.float64) @ ws[int(e)][0].astype(np.float64).T
+    if K:
+        assert rel_l2(hz.to_host_f32(gb.Z[:K]), Z_ref) <= 1e-2
+
+    # --- data gradients on the oracle's dout (rounded to storage) and Z (rounded to bf16)
+    dout_st = store_round(ref["dout"], c.dtype)
+    Z_b = bf16_round(Z_ref)
+    lm.locmoe_expert_ffn_dgrad(desc, rows_dev(dout_st, c.dtype), rows_dev(Z_b, "bf16"), seg_dev, be_dev, W_out_t,
+                               W_in_t, gb.dZ, gb.dsend)
+    torch.cuda.synchronize()
+    dZ_ref = np.zeros((K, c.h)); dsend_ref = np.zeros((K, c.d))
+    for r, e in enumerate(ref["buf_expert"]):
+        a, z = int(ref["seg_off"][r]), int(ref["seg_off"][r + 1])
+        if z > a:
+            Wi, Wo = ws[int(e)]
+            dZ_ref[a:z] = (dout_st[a:z].astype(np.float64) @ Wo.astype(np.float64)) * bwd.gelu_grad(Z_b[a:z])
+            dsend_ref[a:z] = dZ_ref[a:z] @ Wi.astype(np.float64)
+    if K:
+        assert rel_l2(hz.to_host_f32(gb.dZ[:K]), dZ_ref) <= 1e-2
+        assert rel_l2(hz.to_host_f32(gb.dsend[:K]), dsend_ref) <= 1e-2
+
+    # --- weight gradients on the oracle's operands (rounded to what the kernel reads)
+    H_b = bf16_round(orc.gelu(Z_ref))
+    dZ_b = bf16_round(dZ_ref)
+    lm.locmoe_expert_ffn_wgrad(desc, send_dev, rows_dev(H_b, "bf16"), rows_dev(dout_st, c.dtype),
+                               rows_dev(dZ_b, "bf16"), seg_dev, be_dev, gb.dW_in, gb.dW_out)
+    torch.cuda.synchronize()
+    for r, e in enumerate(ref["buf_expert"]):
+        a, z = int(ref["seg_off"][r]), int(ref["seg_off"][r + 1])
+        gi, go = hz.to_host_f32(gb.dW_in[int(e)]), hz.to_host_f32(gb.dW_out[int(e)])
+        if z > a:
+            assert rel_l2(gi, dZ_b[a:z].astype(np.float64).T @ ref["send"][a:z].astype(np.float64)) <= 1e-2
+            assert rel_l2(go, dout_st[a:z].astype(np.float64).T @ H_b[a:z].astype(np.float64)) <= 1e-2
+        else:
+            assert not gi.any() and not go.any()
+
+    # --- router backward on the oracle's g (float32), routing and dw
+    g_dev = torch.from_numpy(ref["g32"]).cuda()
+    cnt_dev = i32(torch, ref["stats"]["cnt"])
+    Psum_dev = torch.from_numpy(ref["stats"]["Psum"].astype(np.float32)).cuda()
+    dw32 = ref["dw"].astype(np.float32)
+    lm.locmoe_route_bwd(desc, g_dev, eps_dev, home_dev, e2n_dev, i32(torch, ref["eid"]), cnt_dev, Psum_dev,
+                        torch.from_numpy(dw32).cuda(), gb.coef, gb.dg)
+    torch.cuda.synchronize()
+    coef_ref = bwd.loss_coefficients(ref["stats"]["cnt"], ref["stats"]["Psum"].astype(np.float32), T, home, e2n_full,
+                                     c.N, alpha, mu)
+    assert np.allclose(gb.coef.cpu().numpy(), coef_ref, rtol=1e-5, atol=1e-12)
+    dg_ref = bwd.route_backward(ref["g32"], eps, relu, ref["eid"], dw32, coef_ref)
+    row_scale = np.abs(coef_ref).max() + np.abs(dw32)
+    assert np.all(np.abs(gb.dg.cpu().numpy() - dg_ref) <= 2e-5 * row_scale[:, None] + 1e-30)
+
+    # --- dispatch + gate backward on the oracle's dsend (rounded to storage) and dg (float32)
+    dsend_st = store_round(ref["dsend"], c.dtype)
+    dg32 = ref["dg"].astype(np.float32)
+    lm.locmoe_dispatch_bwd(desc, rows_dev(dsend_st, c.dtype), slot_dev, torch.from_numpy(dg32).cuda(), gb.dx)
+    torch.cuda.synchronize()
+    dx_ref = bwd.dispatch_backward(dsend_st, ref["slot"]) + bwd.gate_backward(dg32, c.d)
+    assert rel_l2(hz.to_host_f32(gb.dx), dx_ref) <= (1e-2 if c.dtype == "bf16" else 1e-6)
+
+    # --- end to end on the GPU's own intermediates, against the float64 oracle
+    b2, gb2 = lm.alloc_buffers(desc), lm.alloc_grad_buffers(desc)
+    lm.forward_train(desc, x_dev, home_dev, e2n_dev, W_in, W_out, b2, gb2, eps=eps_dev)
+    lm.backward(desc, dy_dev, home_dev, e2n_dev, W_in_t, W_out_t, b2, gb2, eps=eps_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(b2.eid.cpu().numpy(), ref["eid"])
+    errs = {"dx": rel_l2(hz.to_host_f32(gb2.dx), ref["dx"])}
+    gi = np.stack([ref["grads"][e][0] if e in ref["grads"] else np.zeros((c.h, c.d)) for e in range(c.E)])
+    go = np.stack([ref["grads"][e][1] if e in ref["grads"] else np.zeros((c.d, c.h)) for e in range(c.E)])
+    errs["dW_in"] = rel_l2(hz.to_host_f32(gb2.dW_in), gi)
+    errs["dW_out"] = rel_l2(hz.to_host_f32(gb2.dW_out), go)
+    say("      end to end rel-L2: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    for k, v in errs.items():
+        assert v <= 1e-2, (k, v)
+    return errs
+
+
+def test_backward_config1_fp32(env):
+    c = wl.CONFIGS[1]
+    run_backward_case(env, c, c.C)
+
+
+def test_backward_config2_bf16(env):
+    c = wl.CONFIGS[2]
+    run_backward_case(env, c, c.C)
+
+
+def test_backward_small_odd_shapes(env):
+    c = wl.small_config()                     # T=96 d=48 E=6 N=3 h=40: generic kernels everywhere
+    run_backward_case(env, c, 9)
+    run_backward_case(env, c, 200)
+    run_backward_case(env, wl.small_config(dtype="f32"), 5)
+    e2n = np.array([2, 0, 1, 1, 0, 2], np.int32)
+    eps = np.array([0.3, -0.2, 0.0, 0.5, -1.0, 0.1], np.float32)
+    run_backward_case(env, c, 9, eps=eps, e2n=e2n)
+    run_backward_case(env, c, 9, relu=False, use_home=False)
+    run_backward_case(env, wl.small_config(T=5, E=1, N=1, d=8, h=8), 2)
+    run_backward_case(env, wl.small_config(T=300, d=96, E=8, N=2, h=24), 20)      # 12-wide GrAP blocks
+    run_backward_case(env, wl.small_config(T=300, d=96, E=8, N=2, h=24, dtype="f32"), 20)
+
+
+def test_backward_tuned_tiles_with_ragged_segments(env):
+    # 256-multiples: the MFMA weight-gradient kernel; segments with ragged tails, empty experts
+    run_backward_case(env, wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4), 300)
+    run_backward_case(env, wl.small_config(T=2000, d=256, E=16, N=4, h=512, clusters=3), 70)
+    run_backward_case(env, wl.small_config(T=1500, d=768, E=12, N=4, h=256, clusters=3), 33)

@@ -85,6 +85,14 @@ def test_scalar_argument_errors():
     assert L.locmoe_p_delta(8, 1.5, C.byref(out)) == lm.LOCMOE_ERR_ARG
 
 
+def bad_packed_desc(lm, good):
+    return lm.make_desc(**dict(good, w_packed=True))   # shape not packable
+
+
+def zero_c_desc(lm, good):
+    return lm.make_desc(**dict(good, Cap=0))
+
+
 def test_descriptor_validation_without_gpu():
     good = dict(T=64, d=64, E=8, N=2, h=32, Cap=4)
     assert lm.locmoe_workspace_bytes(lm.make_desc(**good)) > 0
@@ -117,6 +125,17 @@ def test_descriptor_validation_without_gpu():
     assert _status(lm.locmoe_dispatch, dsc, p, None, None, p, p, p, p, p, p, p, p, p, 1 << 20, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_expert_ffn, dsc, p, p, p, p, None, p, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_combine_bwd, dsc, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_combine_bwd, zero_c_desc(lm, good), p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
+    assert _status(lm.locmoe_route_bwd, dsc, p, None, None, None, p, p, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_route_bwd, odd, p, None, None, None, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
+    assert _status(lm.locmoe_dispatch_bwd, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_in_save, dsc, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_in_save, bad_packed_desc(lm, good), p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
+    assert _status(lm.locmoe_transpose_weights, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_dgrad, dsc, p, p, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_dgrad, bad_packed_desc(lm, good), p, p, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
+    assert _status(lm.locmoe_expert_ffn_wgrad, dsc, p, p, p, p, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
     # packed weights need 256-multiples of d and h and bf16 activations
     assert lm.locmoe_packed_weights_bytes(dsc) == 0
     big = lm.make_desc(T=64, d=512, E=8, N=2, h=256, Cap=4)
