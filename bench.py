@@ -76,6 +76,57 @@ def cpu_baseline(c, C, x, home, W_in_dev, W_out_dev, budget_rows=4096):
     }
 
 
+def time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in, W_out, stream, reps, K):
+    """Times the backward path (not part of `value`): the forward that keeps Z, then the backward chain, call by
+    call with HIP events on the launch stream.  The transposed (and packed) weights the data gradients read are
+    laid out once, outside the timed calls, and their cost is reported separately (`weight_relayout_ms`): it is
+    paid once per optimizer step, not per batch."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    gb = lm.alloc_grad_buffers(desc)
+    dy = hz.to_device(wl.upstream_grad(c), c.dtype)
+    W_in_t, W_out_t = torch.empty_like(W_out_rm), torch.empty_like(W_in_rm)
+    e0, e1, e2 = ev(), ev(), ev()
+    e0.record(stream)
+    lm.locmoe_transpose_weights(desc, W_in_rm, W_out_rm, W_in_t, W_out_t, stream)
+    e1.record(stream)
+    if desc.w_packed:
+        W_in_tp, W_out_tp = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
+        lm.locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_tp, W_in_tp, stream)
+        W_in_t, W_out_t = W_in_tp, W_out_tp
+    e2.record(stream)
+    torch.cuda.synchronize()
+    relayout = {"transpose": round(e0.elapsed_time(e1), 3), "pack": round(e1.elapsed_time(e2), 3)}
+    names = ["ffn_in_save", "combine_bwd", "dgrad", "wgrad", "route_bwd", "dispatch_bwd"]
+    acc = {n: 0.0 for n in names}
+    total = 0.0
+    for k in range(reps):
+        xs, hs, b = sets[k % len(sets)]
+        lm.forward(desc, xs, hs, None, W_in, W_out, b, stream=stream)
+        evs = [ev() for _ in range(len(names) + 1)]
+        evs[0].record(stream)
+        lm.locmoe_expert_ffn_in_save(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, gb.Z, stream); evs[1].record(stream)
+        lm.locmoe_combine_bwd(desc, dy, b.out, b.slot, b.w, gb.dout, gb.dw, stream); evs[2].record(stream)
+        lm.locmoe_expert_ffn_dgrad(desc, gb.dout, gb.Z, b.seg_off, b.buf_expert, W_out_t, W_in_t, gb.dZ, gb.dsend,
+                                   stream); evs[3].record(stream)
+        lm.locmoe_expert_ffn_wgrad(desc, b.send, b.H, gb.dout, gb.dZ, b.seg_off, b.buf_expert, gb.dW_in, gb.dW_out,
+                                   stream); evs[4].record(stream)
+        lm.locmoe_route_bwd(desc, b.g, None, hs, None, b.eid, b.cnt, b.Psum, gb.dw, gb.coef, gb.dg, stream)
+        evs[5].record(stream)
+        lm.locmoe_dispatch_bwd(desc, gb.dsend, b.slot, gb.dg, gb.dx, stream); evs[6].record(stream)
+        torch.cuda.synchronize()
+        for i, n in enumerate(names):
+            acc[n] += evs[i].elapsed_time(evs[i + 1])
+        total += evs[1].elapsed_time(evs[6])
+    out = {n: round(acc[n] / reps, 4) for n in names}
+    flops = 2.0 * K * c.d * c.h
+    bwd_ms = total / reps
+    return {"ms": out, "backward_ms": round(bwd_ms, 4), "weight_relayout_ms": relayout,
+            "dgrad_TFLOPs": round(2 * flops / (out["dgrad"] * 1e-3) / 1e12, 1),
+            "wgrad_TFLOPs": round(2 * flops / (out["wgrad"] * 1e-3) / 1e12, 1),
+            "wgrad_write_GBps": round(2.0 * c.E * c.d * c.h * 2 / (out["wgrad"] * 1e-3) / 1e9, 1),
+            "note": "backward_ms = combine_bwd .. dispatch_bwd for one batch; ffn_in_save replaces ffn_in in a training forward"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,6 +135,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--sets", type=int, default=4, help="rotating input/buffer sets (defeats cache residency)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward-path timings (reported beside the step)")
     ap.add_argument("--capacity", type=int, default=0, help="override C (0 = Theorem 1 bound at the config's delta)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -203,6 +255,9 @@ def main() -> int:
     for n in est:
         t = est[n] / reps
         estimator[n] = {"ms": round(t, 4), "GB/s": round(est_bytes[n] / (t * 1e-3) / 1e9, 1)}
+    backward = None
+    if not args.no_backward:
+        backward = time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in, W_out, stream, reps, K)
     dom = "ffn_in" if ms["ffn_in"] >= ms["ffn_out"] else "ffn_out"
     achieved = flops / (ms[dom] * 1e-3) / 1e12
     kname = "ffn_gemm_dma_persistent" if desc.w_packed else "ffn_gemm_256"
@@ -225,6 +280,7 @@ def main() -> int:
         "dispatch_hbm_frac": steps_detail["dispatch"]["hbm_frac"],
         "per_step": steps_detail,
         "delta_estimator": estimator,
+        "backward": backward,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -93,6 +93,22 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// ---- direct global -> LDS copies -------------------------------------------------------------
+typedef const char __attribute__((address_space(3))) * lds_cptr;
+
+// One wave-wide 1 KiB copy global -> LDS: lane l reads 16 bytes at sbase + voff and they land at
+// LDS byte address lds_base + 16 l (M0 carries the wave-uniform LDS base).  Default cache policy: nt, sc1
+// and sc0 sc1 on the weight stream all measured equal or slower.
+__device__ __forceinline__ void dma_1k(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase),
+               "s"(lds_base)
+               : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 __host__ __device__ constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }

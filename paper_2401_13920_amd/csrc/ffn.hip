@@ -316,21 +316,6 @@ constexpr int kASlots = 2, kASlotBytes = kBM * kDmaBK * 2 * 2;  // 2 x 32 KiB
 constexpr int kWRing = kASlots * kASlotBytes;                   // weights ring starts after the activations ring
 constexpr int kDmaSmem = kWRing + kWSlots * kWSlotBytes;        // 160 KiB: the whole LDS of a CU
 
-typedef const char __attribute__((address_space(3))) * lds_cptr;
-
-// One wave-wide 1 KiB copy global -> LDS: lane l reads 16 bytes at sbase + voff and they land at
-// LDS byte address lds_base + 16 l (M0 carries the wave-uniform LDS base).  Default cache policy: nt, sc1
-// and sc0 sc1 on the weight stream all measured equal or slower.
-__device__ __forceinline__ void dma_1k(const void* sbase, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase),
-               "s"(lds_base)
-               : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // v_mfma_f32_16x16x32_bf16 with the accumulator pinned to accumulation registers and updated in place.  With all 256
 // of them holding accumulators the compiler's own register assignment routes most MFMAs through a spare
 // tuple (four copies per MFMA); written this way there are none.  The compiler does not see an MFMA here,

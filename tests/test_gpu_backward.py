@@ -222,3 +222,85 @@ def test_backward_tuned_tiles_with_ragged_segments(env):
     run_backward_case(env, wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4), 300)
     run_backward_case(env, wl.small_config(T=2000, d=256, E=16, N=4, h=512, clusters=3), 70)
     run_backward_case(env, wl.small_config(T=1500, d=768, E=12, N=4, h=256, clusters=3), 33)
+
+
+def test_backward_config4_full_size(env):
+    """The headline shape in the benchmark's launch configuration (packed weights, persistent kernels):
+    two whole experts against the oracle (their dout, dsend, dW_in, dW_out and the dx rows of their tokens),
+    dropped tokens, and properties that hold at any size."""
+    import time
+    torch, lm, hz = env
+    c = wl.CONFIGS[4]
+    alpha, mu = wl.ALPHA, wl.MU
+    t0 = time.time()
+    x, home = wl.hidden_states(c)
+    dy = wl.upstream_grad(c)
+    T, C = c.T, c.C
+    say(f"[bwd big] cfg=4 T={T} d={c.d} E={c.E} h={c.h} C={C}; inputs {time.time() - t0:.1f}s")
+    e2n_full = np.arange(c.E) // (c.E // c.N)
+    g32 = orc.gate(x, c.E).astype(np.float32)
+    eid, w, p, _ = orc.route(g32)
+    st = orc.route_stats(eid, p, home, e2n_full, c.N, alpha, mu)
+    s = orc.slots(eid, c.E, C, e2n_full, c.N)
+    K = int(s["seg_off"][-1])
+    kept_cnt = s["kept"]
+    order = np.argsort(kept_cnt)
+    cand = [int(order[-1]), int(order[len(order) // 2])]          # the fullest expert and a median one
+    W_in, W_out, host_w = hz.upload_weights(c, keep=set(cand), progress=lambda a, n: say(f"      weights {a}/{n}"))
+    desc = lm.make_desc(T, c.d, c.E, c.N, c.h, C, c.dtype, True, alpha, mu)
+    W_in_t, W_out_t = torch.empty_like(W_out), torch.empty_like(W_in)
+    lm.locmoe_transpose_weights(desc, W_in, W_out, W_in_t, W_out_t)
+    W_in_p, W_out_p = torch.empty_like(W_in), torch.empty_like(W_out)
+    lm.locmoe_pack_weights(desc, W_in, W_out, W_in_p, W_out_p)
+    W_in_tp, W_out_tp = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
+    lm.locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_tp, W_in_tp)
+    torch.cuda.synchronize()
+    del W_in, W_out, W_in_t, W_out_t
+    desc.w_packed = 1
+    b, gb = lm.alloc_buffers(desc), lm.alloc_grad_buffers(desc)
+    x_dev, dy_dev, home_dev = hz.to_device(x, c.dtype), hz.to_device(dy, c.dtype), i32(torch, home)
+    lm.forward_train(desc, x_dev, home_dev, None, W_in_p, W_out_p, b, gb)
+    lm.backward(desc, dy_dev, home_dev, None, W_in_tp, W_out_tp, b, gb)
+    torch.cuda.synchronize()
+    say(f"      GPU forward + backward done ({time.time() - t0:.1f}s)")
+    assert np.array_equal(b.eid.cpu().numpy(), eid)
+    assert np.array_equal(b.slot.cpu().numpy(), s["slot"])
+    coef = bwd.loss_coefficients(st["cnt"], st["Psum"], T, home, e2n_full, c.N, alpha, mu)
+    assert np.allclose(gb.coef.cpu().numpy(), coef, rtol=1e-4, atol=1e-12)
+    rank_of = {int(e): r for r, e in enumerate(s["buf_expert"])}
+    for e in cand:
+        a, z = int(s["seg_off"][rank_of[e]]), int(s["seg_off"][rank_of[e] + 1])
+        toks = s["row_token"][a:z]
+        Wi, Wo = host_w[e]
+        S = x[toks]
+        out_rows = orc.ffn_rows(S, Wi, Wo)
+        dO = w[toks][:, None] * dy[toks].astype(np.float64)
+        dS, dWi, dWo, _, _ = bwd.ffn_rows_backward(S, Wi, Wo, dO)
+        errs = dict(dout=rel_l2(hz.to_host_f32(gb.dout[a:z]), dO), dsend=rel_l2(hz.to_host_f32(gb.dsend[a:z]), dS),
+                    dW_in=rel_l2(hz.to_host_f32(gb.dW_in[e]), dWi), dW_out=rel_l2(hz.to_host_f32(gb.dW_out[e]), dWo))
+        dw = np.einsum("ij,ij->i", dy[toks].astype(np.float64), out_rows)
+        dg = bwd.route_backward(g32[toks], None, True, eid[toks], dw, coef)
+        dx_ref = dS + bwd.gate_backward(dg, c.d)
+        errs["dx"] = rel_l2(hz.to_host_f32(gb.dx[torch.from_numpy(toks.astype(np.int64)).cuda()]), dx_ref)
+        errs["dw"] = rel_l2(gb.dw.cpu().numpy()[toks], dw)
+        say(f"      expert {e} ({z - a} rows): " + " ".join(f"{k}={v:.2e}" for k, v in errs.items())
+            + f" ({time.time() - t0:.1f}s)")
+        for k, v in errs.items():
+            assert v <= 1e-2, (e, k, v)
+    # dropped tokens: no expert term, dw = 0, only the losses reach the gate
+    dropped = np.nonzero(s["slot"] < 0)[0][:256]
+    if len(dropped):
+        assert not gb.dw.cpu().numpy()[dropped].any()
+        dg = bwd.route_backward(g32[dropped], None, True, eid[dropped], np.zeros(len(dropped)), coef)
+        got = hz.to_host_f32(gb.dx[torch.from_numpy(dropped.astype(np.int64)).cuda()])
+        ref_dx = bwd.gate_backward(dg, c.d)
+        assert np.all(np.abs(got - ref_dx) <= 2.0 ** -8 * np.abs(ref_dx) + 2e-5 * np.abs(coef).max() * c.E / c.d)
+    # any size: each row of dg sums to zero where no ReLU gate is closed (softmax Jacobian annihilates constants)
+    g_all = b.g.cpu().numpy()
+    open_rows = np.nonzero((g_all > 0).all(axis=1))[0][:4096]
+    dg_rows = gb.dg.cpu().numpy()[open_rows]
+    assert np.all(np.abs(dg_rows.sum(axis=1)) <= 1e-5 * np.abs(dg_rows).sum(axis=1) + 1e-12)
+    # an expert's weight gradient is zero exactly when it kept no rows
+    kept_dev = b.kept.cpu().numpy()
+    nz_in = gb.dW_in.float().abs().amax(dim=(1, 2)).cpu().numpy() > 0
+    assert np.array_equal(nz_in, kept_dev > 0)
