@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the two grouped-GEMM kernels at the bench workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (KiB per dispatch; profiles/bench_config4_kernels_and_hbm_counters.txt).  FETCH_SIZE is scaled by 2.0,
 # the factor the same counter needs for a plain 1 GiB copy in the same run; WRITE_SIZE needs none.
-PMC_KIB = {"ffn_in": (4677365.9, 837588.9), "ffn_out": (4934791.6, 210171.6)}
+PMC_KIB = {"ffn_in": (4701538.7, 837588.9), "ffn_out": (4927539.3, 210171.2)}
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
