@@ -33,10 +33,10 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 // 32 B each) then fall into all 64 banks once; with row mod 4 alone half of the LDS cycles were bank conflicts.
 // Rows past the segment's end are read clamped (finite duplicates of the last row) and the P side's copies of
 // them are overwritten with zeros by the wave that fetched them, so their products vanish.
-// Tiles: XCD x (work-groups x mod 8) owns a contiguous eighth of the segment-major tile list, so an expert's
-// operands live in one L2; inside a segment, 32 consecutive tiles (the XCD's work-groups at one time) form a
-// block of 4 m-tiles x 8 n-tiles (12 operand tiles for 32 outputs).  Segments without rows are skipped here
-// and zero-filled by wgrad_zero_empty_kernel.
+// Tiles: XCD x (work-groups x mod 8) owns whole segments, so an expert's operands live in one L2; inside a
+// segment, 32 consecutive tiles (the XCD's work-groups at one time) form a block of 4 m-tiles x 8 n-tiles
+// (12 operand tiles for 32 outputs).  Segments without rows are skipped here and zero-filled by
+// wgrad_zero_empty_kernel.
 constexpr int kWgQBytes = kWgK * kWgTile * 2;   // the Q tile of a step: 32 rows x 256 columns, 16 KiB
 
 struct WgShape {
@@ -94,10 +94,42 @@ __global__ __launch_bounds__(kWgThreads) void wgrad_dma_kernel(
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   lds_cptr lds = (lds_cptr)(uintptr_t)lds0;
 
-  // tile number t of the launch (t mod 8 = XCD) -> position in the segment-major list
+  // Which segments an XCD owns.  With E a multiple of 8 the segments are ranked by descending row count and
+  // dealt to the XCDs in boustrophedon order (ranks 0..7 to XCDs 0..7, ranks 8..15 to XCDs 7..0, ...): every
+  // XCD gets E/8 segments with nearly the same number of rows, largest first (the headline input: 16 % more
+  // steps on the busiest XCD with contiguous eighths of the buffer order, 1 % this way).  Otherwise tile t
+  // simply is tile t of the segment-major list.
+  __shared__ int32_t s_tab[128];  // segment of this XCD's local rank k
+  const bool ranked = (E & 7) == 0;
+  if (ranked) {
+    int32_t* s_seg = (int32_t*)smem;  // [E+1], before the ring is in use
+    for (int t = tid; t <= E; t += kWgThreads) s_seg[t] = seg_off[t];
+    __syncthreads();
+    const int xcd = blockIdx.x & 7;
+    for (int t = tid; t < E; t += kWgThreads) {
+      const int mine = s_seg[t + 1] - s_seg[t];
+      int rank = 0;
+      for (int q = 0; q < E; ++q) {
+        const int other = s_seg[q + 1] - s_seg[q];
+        rank += (other > mine || (other == mine && q < t)) ? 1 : 0;
+      }
+      const int deal = rank >> 3, pos = rank & 7;
+      if (((deal & 1) ? 7 - pos : pos) == xcd) s_tab[deal] = t;
+    }
+    __syncthreads();  // the table is complete and nobody reads the staging area any more
+  }
+
+  // tile number t of the launch (t mod 8 = XCD) -> segment and position inside it
   auto tile_of = [&](int t, int& rows_out) -> WgTile {
-    const int u = (total % 8 == 0) ? (t & 7) * (total >> 3) + (t >> 3) : t;
-    const int r = u / tpe, within = u - r * tpe;
+    int r, within;
+    if (ranked) {
+      const int j = t >> 3, k = j / tpe;  // the XCD's j-th tile lies in its k-th segment
+      r = __builtin_amdgcn_readfirstlane(s_tab[k]);
+      within = j - k * tpe;
+    } else {
+      r = t / tpe;
+      within = t - r * tpe;
+    }
     int mt, nt;
     if (blocked) {
       const int b = within / (MB * 8), i = within % (MB * 8), mb = MT / MB;

@@ -304,3 +304,45 @@ def test_backward_config4_full_size(env):
     kept_dev = b.kept.cpu().numpy()
     nz_in = gb.dW_in.float().abs().amax(dim=(1, 2)).cpu().numpy() > 0
     assert np.array_equal(nz_in, kept_dev > 0)
+
+
+def test_backward_bitwise_repeatable(env):
+    """Every backward result element is written once by one lane and every sum runs in a fixed order:
+    dx, dW_in and dW_out are bit-identical from run to run, for the row-major and the packed-weight kernels."""
+    torch, lm, hz = env
+    c = wl.small_config(T=3000, d=512, E=8, N=2, h=256, clusters=4)
+    x, home = wl.hidden_states(c)
+    dy = wl.upstream_grad(c)
+    ws = {e: wl.expert_weights(c, e) for e in range(c.E)}
+    W_in = torch.stack([hz.to_device(ws[e][0], "bf16") for e in range(c.E)])
+    W_out = torch.stack([hz.to_device(ws[e][1], "bf16") for e in range(c.E)])
+    x_dev, dy_dev, home_dev = hz.to_device(x, c.dtype), hz.to_device(dy, c.dtype), i32(torch, home)
+    for packed in (False, True):
+        desc = lm.make_desc(len(x), c.d, c.E, c.N, c.h, 300, c.dtype, True, 0.3, 0.2)
+        W_in_t, W_out_t = torch.empty_like(W_out), torch.empty_like(W_in)
+        lm.locmoe_transpose_weights(desc, W_in, W_out, W_in_t, W_out_t)
+        Wi, Wo = W_in, W_out
+        if packed:
+            Wi, Wo = torch.empty_like(W_in), torch.empty_like(W_out)
+            lm.locmoe_pack_weights(desc, W_in, W_out, Wi, Wo)
+            Wit, Wot = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
+            lm.locmoe_pack_weights(desc, W_out_t, W_in_t, Wot, Wit)
+            W_in_t, W_out_t = Wit, Wot
+            desc.w_packed = 1
+        runs = []
+        for _ in range(3):
+            b, gb = lm.alloc_buffers(desc), lm.alloc_grad_buffers(desc)
+            lm.forward_train(desc, x_dev, home_dev, None, Wi, Wo, b, gb)
+            lm.backward(desc, dy_dev, home_dev, None, W_in_t, W_out_t, b, gb)
+            torch.cuda.synchronize()
+            runs.append((gb.dx.clone(), gb.dW_in.clone(), gb.dW_out.clone(), gb.dg.clone()))
+        for r in runs[1:]:
+            for a, b_ in zip(runs[0], r):
+                assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a.view(torch.int32),
+                                   b_.view(torch.int16) if b_.dtype == torch.bfloat16 else b_.view(torch.int32))
+        if packed:
+            # the packed-weight kernels against the row-major ones: same arithmetic order per output? not promised;
+            # the bar between them is the oracle's
+            assert rel_l2(hz.to_host_f32(runs[0][0]), hz.to_host_f32(first_dx)) <= 1e-2
+        else:
+            first_dx = runs[0][0]
