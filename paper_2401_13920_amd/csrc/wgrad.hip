@@ -282,7 +282,7 @@ __global__ __launch_bounds__(kWgThreads) void wgrad_dma_kernel(
         for (int p4 = 0; p4 < 4; ++p4) {
           const int row = 4 * p4 + rrow;
           const uint4 v = *(const uint4*)(buf + row * 256 + ((rcol ^ row) << 4));
-          *(uint4*)(Gw + (size_t)(mj * 16 + row) * Ndim + rcol * 8) = v;
+          nt_store16(v, (uint4*)(Gw + (size_t)(mj * 16 + row) * Ndim + rcol * 8));  // written once, read by nobody here
         }
       }
     }
