@@ -92,7 +92,7 @@ def time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in,
     if desc.w_packed:
         W_in_tp, W_out_tp = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
         lm.locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_tp, W_in_tp, stream)
-        W_in_t, W_out_t = W_in_tp, W_out_tp
+        W_in_t, W_out_t = W_in_tp, W_out_tp          # the row-major transposes are released here
     e2.record(stream)
     torch.cuda.synchronize()
     relayout = {"transpose": round(e0.elapsed_time(e1), 3), "pack": round(e1.elapsed_time(e2), 3)}
