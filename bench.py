@@ -85,17 +85,15 @@ def time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in,
     gb = lm.alloc_grad_buffers(desc)
     dy = hz.to_device(wl.upstream_grad(c), c.dtype)
     W_in_t, W_out_t = torch.empty_like(W_out_rm), torch.empty_like(W_in_rm)
-    e0, e1, e2 = ev(), ev(), ev()
+    e0, e1 = ev(), ev()
     e0.record(stream)
-    lm.locmoe_transpose_weights(desc, W_in_rm, W_out_rm, W_in_t, W_out_t, stream)
-    e1.record(stream)
     if desc.w_packed:
-        W_in_tp, W_out_tp = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
-        lm.locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_tp, W_in_tp, stream)
-        W_in_t, W_out_t = W_in_tp, W_out_tp          # the row-major transposes are released here
-    e2.record(stream)
+        lm.locmoe_pack_weights_t(desc, W_in_rm, W_out_rm, W_in_t, W_out_t, stream)   # transposed and packed in one pass
+    else:
+        lm.locmoe_transpose_weights(desc, W_in_rm, W_out_rm, W_in_t, W_out_t, stream)
+    e1.record(stream)
     torch.cuda.synchronize()
-    relayout = {"transpose": round(e0.elapsed_time(e1), 3), "pack": round(e1.elapsed_time(e2), 3)}
+    relayout = round(e0.elapsed_time(e1), 3)
     names = ["ffn_in_save", "combine_bwd", "dgrad", "wgrad", "route_bwd", "dispatch_bwd"]
     acc = {n: 0.0 for n in names}
     total = 0.0

@@ -228,6 +228,13 @@ int locmoe_expert_ffn_in_save(const locmoe_desc* desc, const void* send, const i
 int locmoe_transpose_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_t,
                              void* W_out_t, void* stream);
 
+/* The packed layout (as locmoe_pack_weights writes it) of the transposed weights, straight from the row-major
+ * weights in one pass: same result as locmoe_transpose_weights followed by
+ * locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_t_packed, W_in_t_packed), bit for bit, without the row-major
+ * transposes in between.  Same shape conditions and errors as locmoe_pack_weights. */
+int locmoe_pack_weights_t(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_t_packed,
+                          void* W_out_t_packed, void* stream);
+
 /* Eq. 1, backward with respect to the rows (data gradients), two grouped GEMMs like the forward:
  *   dZ[r,:]    = (W_out[e]^T . dout[r,:]) * GeLU'(Z[r,:])   (bf16; GeLU'(v) = Phi(v) + v phi(v))
  *   dsend[r,:] = W_in[e]^T . dZ[r,:]                        (x_dtype)

@@ -34,24 +34,6 @@ __device__ __forceinline__ float dot16(const uint4& a, const uint4& b) {
   return fmaf(__uint_as_float(a.w), __uint_as_float(b.w), s);
 }
 
-template <bool BF16>
-__device__ __forceinline__ uint4 scaled16(const uint4& v, float w) {
-  uint4 r;
-  if (BF16) {
-    const uint32_t* p = &v.x;
-    uint32_t* q = &r.x;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      q[i] = pack_bf16x2(w * bf16_bits_to_f32(p[i] & 0xFFFFu), w * __uint_as_float(p[i] & 0xFFFF0000u));
-  } else {
-    r.x = __float_as_uint(w * __uint_as_float(v.x));
-    r.y = __float_as_uint(w * __uint_as_float(v.y));
-    r.z = __float_as_uint(w * __uint_as_float(v.z));
-    r.w = __float_as_uint(w * __uint_as_float(v.w));
-  }
-  return r;
-}
-
 // One wave per token row.  A dropped token reads nothing and gets dw = 0.
 template <bool BF16>
 __global__ __launch_bounds__(kBwdThreads) void combine_bwd_kernel(const uint4* __restrict__ dy,
@@ -82,13 +64,13 @@ __global__ __launch_bounds__(kBwdThreads) void combine_bwd_kernel(const uint4* _
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       acc += dot16<BF16>(va[u], vb[u]);
-      nt_store16(scaled16<BF16>(va[u], wm), dst + c + u * kWave);
+      nt_store16(scale16<BF16>(va[u], wm), dst + c + u * kWave);
     }
   }
   for (; c < chunks; c += kWave) {
     const uint4 va = nt_load16(a + c), vb = nt_load16(b + c);
     acc += dot16<BF16>(va, vb);
-    nt_store16(scaled16<BF16>(va, wm), dst + c);
+    nt_store16(scale16<BF16>(va, wm), dst + c);
   }
   acc = group_sum<kWave>(acc);
   if (l == 0) dw[m] = acc;

@@ -8,24 +8,6 @@ namespace {
 
 constexpr int kCombThreads = 256;
 
-template <bool BF16>
-__device__ __forceinline__ uint4 scale16(const uint4& v, float w) {
-  uint4 r;
-  if (BF16) {
-    const uint32_t* p = &v.x;
-    uint32_t* q = &r.x;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      q[i] = pack_bf16x2(w * bf16_bits_to_f32(p[i] & 0xFFFFu), w * __uint_as_float(p[i] & 0xFFFF0000u));
-  } else {
-    r.x = __float_as_uint(w * __uint_as_float(v.x));
-    r.y = __float_as_uint(w * __uint_as_float(v.y));
-    r.z = __float_as_uint(w * __uint_as_float(v.z));
-    r.w = __float_as_uint(w * __uint_as_float(v.w));
-  }
-  return r;
-}
-
 // LPR lanes share one token row of `chunks` 16-byte vectors; one block per group of rows.  Measured at the
 // headline shape (8 KiB rows): many lanes per row with one or two chunks each beats fewer lanes with deeper
 // unrolling, and a grid-stride loop is slower than one short-lived block per row group.

@@ -65,6 +65,25 @@ __device__ __forceinline__ float sumsq4_f32(const uint4& v) {
   return (a * a + b * b) + (c * c + d * d);
 }
 
+// v * w for the 4 fp32 or 8 bf16 values of a 16-byte vector (products in fp32, rounded to the storage type)
+template <bool BF16>
+__device__ __forceinline__ uint4 scale16(const uint4& v, float w) {
+  uint4 r;
+  if (BF16) {
+    const uint32_t* p = &v.x;
+    uint32_t* q = &r.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      q[i] = pack_bf16x2(w * bf16_bits_to_f32(p[i] & 0xFFFFu), w * __uint_as_float(p[i] & 0xFFFF0000u));
+  } else {
+    r.x = __float_as_uint(w * __uint_as_float(v.x));
+    r.y = __float_as_uint(w * __uint_as_float(v.y));
+    r.z = __float_as_uint(w * __uint_as_float(v.z));
+    r.w = __float_as_uint(w * __uint_as_float(v.w));
+  }
+  return r;
+}
+
 // ---- cross-lane moves on the DPP path (no LDS traffic) ------------------------------------
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
@@ -116,6 +135,9 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? LOCMOE_OK 
 
 // host-side validation shared by the entry points
 int check_desc(const locmoe_desc* d);
+// compute units of the current device (the grid of the persistent kernels), 256 if the query fails; asked once
+// per device
+int cu_count();
 
 // route / dispatch scratch layout (see workspace.cpp)
 constexpr int kRouteMaxBlocks = 512;     // upper bound of route blocks (partials per block)

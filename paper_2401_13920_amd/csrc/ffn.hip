@@ -747,17 +747,50 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint4* __restri
   Wp[q] = W[src];
 }
 
-// compute units of the current device (the persistent kernel's grid), 256 if the query fails; asked once per device
-inline int cu_count() {
-  static std::atomic<int> cached[64];
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  int n = cached[dev].load(std::memory_order_relaxed);
-  if (n == 0) {
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-    cached[dev].store(n, std::memory_order_relaxed);
+// The packed layout of W^T straight from the row-major W [Rk rows, Cn columns] (the data gradients contract
+// with the transposes): block (e, nt, kt) is the LDS image of W^T[nt*256 .. +256][kt*32 .. +32], i.e. of the
+// 32 x 256 piece W[kt*32 ..][nt*256 ..].  The piece goes through LDS (512-byte rows, chunk index XORed with a
+// 3-bit function of the row) and comes back through gfx950's transposing LDS read: 16 lanes receive the 8
+// k-values of 16 consecutive columns, which is one 16-byte chunk of the packed block per lane.
+typedef __attribute__((ext_vector_type(4))) short pk_s16x4;
+__global__ __launch_bounds__(256) void transpose_pack_kernel(const uint16_t* __restrict__ W, uint4* __restrict__ Xp,
+                                                             int Rk, int Cn) {
+  __shared__ __attribute__((aligned(16))) char tile[32 * 512];
+  const int KT = Rk / kDmaBK, NT = Cn / kBN;
+  int blk = blockIdx.x;
+  const int kt = blk % KT; blk /= KT;
+  const int nt = blk % NT;
+  const int e = blk / NT;
+  const int t = threadIdx.x;
+  const uint16_t* src = W + ((size_t)e * Rk + (size_t)kt * kDmaBK) * Cn + (size_t)nt * kBN;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = t + 256 * i, r = c >> 5, cc = c & 31;
+    const uint4 v = *(const uint4*)(src + (size_t)r * Cn + cc * 8);
+    const int sw = (r & 3) | (((r >> 3) & 1) << 2);
+    *(uint4*)(tile + r * 512 + ((cc ^ (sw << 1)) << 4)) = v;
   }
-  return n;
+  __syncthreads();
+  const int lane = t & 63, wave = t >> 6, g = lane >> 4, s16 = lane & 15;
+  const int sw = (s16 >> 2) | ((g & 1) << 2);
+  const int row = 8 * g + (s16 >> 2), b1 = (s16 & 3) >> 1, inner = (s16 & 1) * 8;
+  uint4* dst = Xp + (size_t)blockIdx.x * 1024;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int nbase = 16 * (wave + 4 * it);
+    const char* p = tile + row * 512 + ((((nbase >> 3) + b1) ^ (sw << 1)) << 4) + inner;
+    const pk_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((pk_s16x4 __attribute__((address_space(3)))*)p);
+    const pk_s16x4 hi =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((pk_s16x4 __attribute__((address_space(3)))*)(p + 4 * 512));
+    // this lane now holds W^T[n][8 g .. 8 g + 7] for n = nbase + s16: k-chunk g of packed row n
+    const int n = nbase + s16;
+    uint4 v;
+    v.x = (uint32_t)(uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+    v.y = (uint32_t)(uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+    v.z = (uint32_t)(uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+    v.w = (uint32_t)(uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+    dst[n * 4 + (g ^ ((n >> 1) & 3))] = v;
+  }
 }
 
 // names a launch's tile queues; one sequence for every instantiation of the kernel
@@ -959,6 +992,24 @@ extern "C" int locmoe_transpose_weights(const locmoe_desc* desc, const void* W_i
                      (uint16_t*)W_in_t, desc->h, desc->d);
   hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles_h, tiles_d, desc->E), dim3(256), 0, s, (const uint16_t*)W_out,
                      (uint16_t*)W_out_t, desc->d, desc->h);
+  return launch_status();
+}
+
+extern "C" int locmoe_pack_weights_t(const locmoe_desc* desc, const void* W_in, const void* W_out,
+                                     void* W_in_t_packed, void* W_out_t_packed, void* stream) {
+  using namespace locmoe;
+  if (!desc || !W_in || !W_out || !W_in_t_packed || !W_out_t_packed) return LOCMOE_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  if (!packable(desc)) return LOCMOE_ERR_SHAPE;
+  const long long blocks = (long long)desc->E * (desc->h / kBN) * (desc->d / kDmaBK);  // = E (d/256) (h/32) as well
+  if (blocks > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
+  hipStream_t s = as_stream(stream);
+  // W_in[e] is [h,d]: its transpose has N = d rows and K = h;  W_out[e] is [d,h]: N = h, K = d
+  hipLaunchKernelGGL(transpose_pack_kernel, dim3((unsigned)((long long)desc->E * (desc->d / kBN) * (desc->h / kDmaBK))),
+                     dim3(256), 0, s, (const uint16_t*)W_in, (uint4*)W_in_t_packed, desc->h, desc->d);
+  hipLaunchKernelGGL(transpose_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint16_t*)W_out,
+                     (uint4*)W_out_t_packed, desc->d, desc->h);
   return launch_status();
 }
 

@@ -1,5 +1,6 @@
 // Host-only part of liblocmoe: status strings, descriptor validation, the scalar capacity
 // formulas of Section 3.2.3 (Lemma 3, Theorem 1) and the workspace size.
+#include <atomic>
 #include <cmath>
 #include <limits>
 
@@ -19,6 +20,18 @@ int check_desc(const locmoe_desc* p) {
   if (p->w_packed != 0 && p->w_packed != 1) return LOCMOE_ERR_ARG;
   if ((int64_t)p->E * (int64_t)p->C > (int64_t)std::numeric_limits<int32_t>::max()) return LOCMOE_ERR_SHAPE;
   return LOCMOE_OK;
+}
+
+int cu_count() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
 }
 
 namespace {

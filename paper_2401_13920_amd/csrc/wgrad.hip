@@ -328,14 +328,6 @@ __global__ __launch_bounds__(256) void wgrad_generic_kernel(const void* __restri
   G[((size_t)buf_expert[r] * Mdim + m) * Ndim + n] = f32_to_bf16_bits(s);
 }
 
-inline int wg_cu_count() {
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
-    return 256;
-  return n;
-}
-
 template <bool P_F32, bool Q_F32>
 int launch_wgrad(const void* P, const void* Q, void* G, const int32_t* seg_off, const int32_t* buf_expert, int E,
                  int rows_max, int Mdim, int Ndim, hipStream_t st) {
@@ -351,7 +343,7 @@ int launch_wgrad(const void* P, const void* Q, void* G, const int32_t* seg_off, 
       hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, E), dim3(256), 0, st, (uint4*)G, seg_off, buf_expert,
                          chunks);
       const long long tiles = (long long)E * (Mdim / S::kTM) * (Ndim / kWgTile);
-      const long long groups = std::min<long long>((wg_cu_count() / 8) * 8, (tiles + 7) / 8 * 8);
+      const long long groups = std::min<long long>((cu_count() / 8) * 8, (tiles + 7) / 8 * 8);
       hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kWgThreads), S::kSmem, st, (const uint16_t*)P,
                          (const uint16_t*)Q, (uint16_t*)G, seg_off, buf_expert, Mdim, Ndim, E);
       return launch_status();

@@ -25,7 +25,7 @@ EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "loc
            "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine",
            "locmoe_packed_weights_bytes", "locmoe_pack_weights", "locmoe_combine_bwd", "locmoe_route_bwd",
            "locmoe_dispatch_bwd", "locmoe_expert_ffn_in_save", "locmoe_transpose_weights",
-           "locmoe_expert_ffn_dgrad", "locmoe_expert_ffn_wgrad")
+           "locmoe_expert_ffn_dgrad", "locmoe_expert_ffn_wgrad", "locmoe_pack_weights_t")
 
 
 class locmoe_desc(C.Structure):
@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
     L.locmoe_dispatch_bwd.argtypes = [D] + [P] * 5
     L.locmoe_expert_ffn_in_save.argtypes = [D] + [P] * 7
     L.locmoe_transpose_weights.argtypes = [D] + [P] * 5
+    L.locmoe_pack_weights_t.argtypes = [D] + [P] * 5
     L.locmoe_expert_ffn_dgrad.argtypes = [D] + [P] * 9
     L.locmoe_expert_ffn_wgrad.argtypes = [D] + [P] * 9
     L.locmoe_packed_weights_bytes.restype = SZ
@@ -229,6 +230,11 @@ def locmoe_expert_ffn_in_save(desc, send, seg_off, buf_expert, W_in, H_ws, Z, st
 def locmoe_transpose_weights(desc, W_in, W_out, W_in_t, W_out_t, stream=None):
     _check(lib().locmoe_transpose_weights(C.byref(desc), _ptr(W_in), _ptr(W_out), _ptr(W_in_t), _ptr(W_out_t),
                                           _stream(stream)))
+
+
+def locmoe_pack_weights_t(desc, W_in, W_out, W_in_t_packed, W_out_t_packed, stream=None):
+    _check(lib().locmoe_pack_weights_t(C.byref(desc), _ptr(W_in), _ptr(W_out), _ptr(W_in_t_packed),
+                                       _ptr(W_out_t_packed), _stream(stream)))
 
 
 def locmoe_expert_ffn_dgrad(desc, dout, Z, seg_off, buf_expert, W_out_t, W_in_t, dZ, dsend, stream=None):

@@ -327,6 +327,12 @@ def test_backward_bitwise_repeatable(env):
             lm.locmoe_pack_weights(desc, W_in, W_out, Wi, Wo)
             Wit, Wot = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
             lm.locmoe_pack_weights(desc, W_out_t, W_in_t, Wot, Wit)
+            # the one-pass form gives the same bits
+            Wit1, Wot1 = torch.zeros_like(Wit), torch.zeros_like(Wot)
+            lm.locmoe_pack_weights_t(desc, W_in, W_out, Wit1, Wot1)
+            torch.cuda.synchronize()
+            assert torch.equal(Wit1.view(torch.int16), Wit.view(torch.int16))
+            assert torch.equal(Wot1.view(torch.int16), Wot.view(torch.int16))
             W_in_t, W_out_t = Wit, Wot
             desc.w_packed = 1
         runs = []

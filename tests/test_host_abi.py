@@ -133,6 +133,8 @@ def test_descriptor_validation_without_gpu():
     assert _status(lm.locmoe_expert_ffn_in_save, dsc, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_expert_ffn_in_save, bad_packed_desc(lm, good), p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
     assert _status(lm.locmoe_transpose_weights, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_pack_weights_t, dsc, p, p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
+    assert _status(lm.locmoe_pack_weights_t, lm.make_desc(T=64, d=512, E=8, N=2, h=256, Cap=4), p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_expert_ffn_dgrad, dsc, p, p, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_expert_ffn_dgrad, bad_packed_desc(lm, good), p, p, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG
     assert _status(lm.locmoe_expert_ffn_wgrad, dsc, p, p, p, p, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
