@@ -352,3 +352,15 @@ def test_backward_bitwise_repeatable(env):
             assert rel_l2(hz.to_host_f32(runs[0][0]), hz.to_host_f32(first_dx)) <= 1e-2
         else:
             first_dx = runs[0][0]
+
+
+def test_backward_expert_count_limits(env):
+    # the largest expert count the ABI allows (1-wide GrAP blocks, 16 experts per lane in the router backward)
+    run_backward_case(env, wl.small_config(T=700, d=1024, E=1024, N=32, h=8, clusters=7), 2)
+    # one node, capacity of a single row: almost every token is dropped and only the losses reach the gate
+    run_backward_case(env, wl.small_config(T=257, d=64, E=64, N=1, h=16, clusters=3), 1)
+    # a free-form expert-to-node map with more nodes than experts per node, E no multiple of 8
+    e2n = (np.arange(12) * 5 % 7).astype(np.int32)
+    run_backward_case(env, wl.small_config(T=513, d=96, E=12, N=7, h=24, clusters=4), 11, e2n=e2n)
+    # 200 experts (several per lane group, E/4 units not a power of two), wide experts with LDS gate path
+    run_backward_case(env, wl.small_config(T=1111, d=1600, E=200, N=8, h=16, clusters=9), 3)
