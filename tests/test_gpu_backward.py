@@ -224,19 +224,18 @@ def test_backward_tuned_tiles_with_ragged_segments(env):
     run_backward_case(env, wl.small_config(T=1500, d=768, E=12, N=4, h=256, clusters=3), 33)
 
 
-def test_backward_config4_full_size(env):
-    """The headline shape in the benchmark's launch configuration (packed weights, persistent kernels):
+def run_backward_big(env, c, C):
+    """A full-size shape in the benchmark's launch configuration (packed weights, persistent kernels):
     two whole experts against the oracle (their dout, dsend, dW_in, dW_out and the dx rows of their tokens),
     dropped tokens, and properties that hold at any size."""
     import time
     torch, lm, hz = env
-    c = wl.CONFIGS[4]
     alpha, mu = wl.ALPHA, wl.MU
     t0 = time.time()
     x, home = wl.hidden_states(c)
     dy = wl.upstream_grad(c)
-    T, C = c.T, c.C
-    say(f"[bwd big] cfg=4 T={T} d={c.d} E={c.E} h={c.h} C={C}; inputs {time.time() - t0:.1f}s")
+    T = c.T
+    say(f"[bwd big] cfg={c.cfg} T={T} d={c.d} E={c.E} h={c.h} C={C}; inputs {time.time() - t0:.1f}s")
     e2n_full = np.arange(c.E) // (c.E // c.N)
     g32 = orc.gate(x, c.E).astype(np.float32)
     eid, w, p, _ = orc.route(g32)
@@ -364,3 +363,14 @@ def test_backward_expert_count_limits(env):
     run_backward_case(env, wl.small_config(T=513, d=96, E=12, N=7, h=24, clusters=4), 11, e2n=e2n)
     # 200 experts (several per lane group, E/4 units not a power of two), wide experts with LDS gate path
     run_backward_case(env, wl.small_config(T=1111, d=1600, E=200, N=8, h=16, clusters=9), 3)
+
+
+def test_backward_config4_full_size(env):
+    c = wl.CONFIGS[4]
+    run_backward_big(env, c, c.C)
+
+
+def test_backward_config3_full_size_nothing_dropped(env):
+    """Capacity above every count: segments of thousands of rows (many m-tiles per weight tile in the data
+    gradients, a hundred steps per tile in the weight gradients), very uneven."""
+    run_backward_big(env, wl.CONFIGS[3], 2048)
