@@ -165,7 +165,10 @@ int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* 
  * State: the packed-weight kernels (E a multiple of 8, at most 512) hand out tiles through queue words
  * in a small device array that the library owns (no allocation; 64 sets, taken round-robin per launch
  * and cleared by the launch itself).  Launches may overlap on other streams or host threads as long as
- * fewer than 64 of them are in flight on one device.  Every other entry point is stateless. */
+ * fewer than 64 of them are in flight on one device.  Every other entry point is stateless.
+ * No entry point allocates, clears memory or waits for the device, so calls may be recorded into a HIP graph;
+ * a recorded packed-weight launch keeps the queue set it was given, so replays of graphs that contain the same
+ * recorded launch must not overlap one another (replays on one stream do not). */
 size_t locmoe_packed_weights_bytes(const locmoe_desc* desc);
 int locmoe_pack_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_packed,
                         void* W_out_packed, void* stream);
