@@ -545,8 +545,10 @@ def test_config4_full_size_headline(env):
 
 
 def test_config5_full_size_routing_stress(env):
+    """The largest configuration: adversarial routing (four hot experts), 128 experts = 16 segments per XCD queue
+    of the persistent GEMM, d = 5120 (20 column tiles); FFN rows sampled as at config 4."""
     c = wl.CONFIGS[5]
-    run_big(env, c, c.C, with_ffn=False)
+    run_big(env, c, c.C, with_ffn=True)
 
 
 def test_config4_full_size_angles(env):
