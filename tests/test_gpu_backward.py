@@ -370,7 +370,7 @@ def test_backward_config4_full_size(env):
     run_backward_big(env, c, c.C)
 
 
-def test_backward_config3_full_size_nothing_dropped(env):
-    """Capacity above every count: segments of thousands of rows (many m-tiles per weight tile in the data
+def test_backward_config3_full_size_large_capacity(env):
+    """Capacity 2 048 (almost nothing dropped): segments of up to 2 048 rows (many m-tiles per weight tile in the data
     gradients, a hundred steps per tile in the weight gradients), very uneven."""
     run_backward_big(env, wl.CONFIGS[3], 2048)

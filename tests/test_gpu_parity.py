@@ -539,6 +539,11 @@ def test_config3_full_size_capacity_sweep(env):
         check_dispatch(env, c, desc, b, x, x_dev, eid, None, C)
 
 
+def test_config3_full_size_large_capacity(env):
+    """Capacity 2 048 (116 of 32 768 tokens dropped): segments of up to 2 048 rows, eight row tiles per weight tile."""
+    run_big(env, wl.CONFIGS[3], 2048)
+
+
 def test_config4_full_size_headline(env):
     c = wl.CONFIGS[4]
     run_big(env, c, c.C)
