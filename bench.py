@@ -122,6 +122,11 @@ def time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in,
             "dgrad_TFLOPs": round(2 * flops / (out["dgrad"] * 1e-3) / 1e12, 1),
             "wgrad_TFLOPs": round(2 * flops / (out["wgrad"] * 1e-3) / 1e12, 1),
             "wgrad_write_GBps": round(2.0 * c.E * c.d * c.h * 2 / (out["wgrad"] * 1e-3) / 1e9, 1),
+            "roofline": {"bound": "mfma", "kernel": "wgrad_dma_kernel (two launches per step)" if desc.w_packed else "wgrad",
+                         "achieved": round(2 * flops / (out["wgrad"] * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s",
+                         "frac": round(2 * flops / (out["wgrad"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "flops_per_launch": flops, "bytes_written_per_launch": c.E * c.d * c.h * 2},
             "note": "backward_ms = combine_bwd .. dispatch_bwd for one batch; ffn_in_save replaces ffn_in in a training forward"}
 
 
