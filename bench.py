@@ -258,6 +258,31 @@ def main() -> int:
     for n in est:
         t = est[n] / reps
         estimator[n] = {"ms": round(t, 4), "GB/s": round(est_bytes[n] / (t * 1e-3) / 1e9, 1)}
+    # the two GEMMs with every expert at capacity (K = E*C rows, the shape the roofline target of the FFN is
+    # stated for): token rows stand in for the send buffer, so the operands have the statistics of real ones
+    full = None
+    if desc.w_packed and c.E * C <= c.T:
+        Kf = c.E * C
+        seg_full = torch.arange(c.E + 1, dtype=torch.int32, device="cuda") * C
+        be_full = torch.arange(c.E, dtype=torch.int32, device="cuda")
+        send_full = sets[0][0][:Kf].contiguous()
+        Hf = torch.empty(Kf, c.h, dtype=torch.bfloat16, device="cuda")
+        of = torch.empty(Kf, c.d, dtype=send_full.dtype, device="cuda")
+        accf = [0.0, 0.0]
+        for k in range(reps + 2):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ev[0].record(stream)
+            lm.locmoe_expert_ffn_in(desc, send_full, seg_full, be_full, W_in, Hf, stream); ev[1].record(stream)
+            lm.locmoe_expert_ffn_out(desc, Hf, seg_full, be_full, W_out, of, stream); ev[2].record(stream)
+            torch.cuda.synchronize()
+            if k >= 2:
+                accf[0] += ev[0].elapsed_time(ev[1]); accf[1] += ev[1].elapsed_time(ev[2])
+        ff = 2.0 * Kf * c.d * c.h
+        full = {"K": Kf, "ffn_in_ms": round(accf[0] / reps, 4), "ffn_out_ms": round(accf[1] / reps, 4),
+                "ffn_in_TFLOPs": round(ff / (accf[0] / reps * 1e-3) / 1e12, 1),
+                "ffn_out_TFLOPs": round(ff / (accf[1] / reps * 1e-3) / 1e12, 1),
+                "mfma_frac_both": round(2 * ff / ((accf[0] + accf[1]) / reps * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        del send_full, Hf, of
     backward = None
     if not args.no_backward:
         backward = time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in, W_out, stream, reps, K)
@@ -282,6 +307,7 @@ def main() -> int:
         "dispatch_GBps": steps_detail["dispatch"]["GB/s"],
         "dispatch_hbm_frac": steps_detail["dispatch"]["hbm_frac"],
         "per_step": steps_detail,
+        "ffn_every_expert_at_capacity": full,
         "delta_estimator": estimator,
         "backward": backward,
         "roofline": roofline,
