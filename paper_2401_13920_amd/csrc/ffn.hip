@@ -625,9 +625,9 @@ __device__ __forceinline__ void leave_queues(unsigned int* queue, unsigned group
 // 512-thread, 160 KiB group, the ordering preamble and a cold pipeline; for segments of at most 256 rows
 // (no second m-tile to share the weight stream with) that was a third of the time.
 //
-// Which tiles.  Work-groups with ids congruent mod 8 run on one XCD (one L2).  XCD x owns the segments
-// whose rank in descending order of row count is congruent to x and queues their tiles largest segment
-// first; only non-empty tiles are enumerated, all tiles of a segment together with the m-tiles that share
+// Which tiles.  Work-groups with ids congruent mod 8 run on one XCD (one L2).  The segments, ranked by
+// descending row count, are dealt to the XCDs eight at a time in alternating direction; an XCD queues the
+// tiles of its segments largest segment first; only non-empty tiles are enumerated, all tiles of a segment together with the m-tiles that share
 // a weight tile adjacent.  The XCD's gridDim/8 work-groups start on the first gridDim/8 tiles and claim
 // further ones from the queue (one atomic add per tile, issued before the epilogue and consumed after it,
 // one tile ahead of the one being computed),
@@ -660,7 +660,10 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
       const int other = s_seg[q + 1] - s_seg[q];
       rank += (other > mine || (other == mine && q < t)) ? 1 : 0;
     }
-    if ((rank & 7) == xcd) s_tab[rank >> 3] = t;
+    // dealt in boustrophedon order (ranks 0..7 to XCDs 0..7, ranks 8..15 to XCDs 7..0, ...): every XCD gets
+    // nearly the same number of rows; plain rank mod 8 always hands XCD 0 the largest of eight (+5 % rows on
+    // the headline input, 1.3 % of the step's time)
+    if ((((rank >> 3) & 1) ? 7 - (rank & 7) : (rank & 7)) == xcd) s_tab[rank >> 3] = t;
   }
   __syncthreads();
   int tab_seg = 0, tab_cum = 0;  // lane k < nloc: segment of local rank k, tiles of local ranks 0..k
