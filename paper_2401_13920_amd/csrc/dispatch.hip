@@ -73,8 +73,8 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
       const int e = e0 + (R > 1 ? tid % E : tid), rg = R > 1 ? tid / E : 0;
       int before = 0, all = 0;
       if (e < E && rg < R) {
-#pragma unroll 4
-        for (int q = rg; q < nblocks; q += R) {
+#pragma unroll 16
+        for (int q = rg; q < nblocks; q += R) {  // (independent loads: all of an unrolled batch are in flight together)
           const int c = blockcnt[(size_t)q * E + e];
           before += q < b ? c : 0;
           all += c;
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
 // send[r,:] = x[row_token[r],:].  A row is `chunks` 16-byte vectors; LPR lanes share a row.  Blocks walk the
 // K kept rows with a grid stride; the token index of the next row is fetched before the current row is
 // copied, so the index -> row dependency is off the critical path.
-constexpr int kCopyBlocksPerCu = 8, kCus = 256;
+constexpr int kCopyBlocksPerCu = 8;
 
 template <int LPR>
 __global__ __launch_bounds__(kDispThreads) void dispatch_copy_kernel(const uint4* __restrict__ x,
@@ -235,33 +235,22 @@ template <int LPR>
 void launch_copy(const void* x, const int32_t* row_token, const int32_t* seg_off, void* send, int E, int rows,
                  int chunks, hipStream_t st) {
   constexpr int RPB = kDispThreads / LPR;
-  const int blocks = min(ceil_div(rows, RPB), kCus * kCopyBlocksPerCu);
+  const int blocks = min(ceil_div(rows, RPB), cu_count() * kCopyBlocksPerCu);
   hipLaunchKernelGGL((dispatch_copy_kernel<LPR>), dim3(blocks), dim3(kDispThreads), 0, st, (const uint4*)x,
                      row_token, seg_off, (uint4*)send, E, chunks);
 }
 
-}  // namespace
-}  // namespace locmoe
 
-extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n,
-                               int32_t* pos, int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off,
-                               int32_t* buf_expert, int32_t* row_token, void* send, void* ws, size_t ws_bytes,
-                               void* stream) {
-  using namespace locmoe;
-  if (!desc || !x || !eid || !pos || !slot || !kept || !seg_off || !node_off || !buf_expert || !row_token ||
-      !send)
-    return LOCMOE_ERR_NULL;
-  int st = check_desc(desc);
-  if (st != LOCMOE_OK) return st;
-  if (!e2n && desc->E % desc->N != 0) return LOCMOE_ERR_SHAPE;
-  if (!ws || ws_bytes < locmoe_workspace_bytes(desc)) return LOCMOE_ERR_WORKSPACE;
-  hipStream_t s = as_stream(stream);
+// The three launches of the dispatch; `blockcnt` holds ceil(T/1024) x E counts (every one is written by the first
+// kernel before the second reads it: nothing has to be cleared).
+int dispatch_launch(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n, int32_t* pos,
+                    int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off, int32_t* buf_expert,
+                    int32_t* row_token, void* send, int32_t* blockcnt, hipStream_t s) {
   const int T = desc->T, E = desc->E;
   const int nblocks = ceil_div(T, kDispatchTokensPerBlock);
-  int32_t* blockcnt = (int32_t*)ws;
   hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblocks), dim3(kDispThreads), (size_t)E * 4, s, eid, blockcnt, T,
                      E);
-  st = launch_status();
+  int st = launch_status();
   if (st != LOCMOE_OK) return st;
   int nbits = 0;
   while ((1 << nbits) < E) ++nbits;
@@ -283,4 +272,31 @@ extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int
   else if (chunks >= 64) launch_copy<16>(x, row_token, seg_off, send, E, rows, chunks, s);
   else launch_copy<8>(x, row_token, seg_off, send, E, rows, chunks, s);
   return launch_status();
+}
+
+int dispatch_check(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n, int32_t* pos,
+                   int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off, int32_t* buf_expert,
+                   int32_t* row_token, void* send) {
+  if (!desc || !x || !eid || !pos || !slot || !kept || !seg_off || !node_off || !buf_expert || !row_token ||
+      !send)
+    return LOCMOE_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  if (!e2n && desc->E % desc->N != 0) return LOCMOE_ERR_SHAPE;
+  return LOCMOE_OK;
+}
+
+}  // namespace
+}  // namespace locmoe
+
+extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n,
+                               int32_t* pos, int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off,
+                               int32_t* buf_expert, int32_t* row_token, void* send, void* ws, size_t ws_bytes,
+                               void* stream) {
+  using namespace locmoe;
+  const int st = dispatch_check(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_expert, row_token, send);
+  if (st != LOCMOE_OK) return st;
+  if (!ws || ws_bytes < locmoe_workspace_bytes(desc)) return LOCMOE_ERR_WORKSPACE;
+  return dispatch_launch(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_expert, row_token, send,
+                         (int32_t*)ws, as_stream(stream));
 }

@@ -247,20 +247,29 @@ def run_backward_big(env, c, C):
     cand = [int(order[-1]), int(order[len(order) // 2])]          # the fullest expert and a median one
     W_in, W_out, host_w = hz.upload_weights(c, keep=set(cand), progress=lambda a, n: say(f"      weights {a}/{n}"))
     desc = lm.make_desc(T, c.d, c.E, c.N, c.h, C, c.dtype, True, alpha, mu)
-    W_in_t, W_out_t = torch.empty_like(W_out), torch.empty_like(W_in)
-    lm.locmoe_transpose_weights(desc, W_in, W_out, W_in_t, W_out_t)
+    # packed transposes straight from the row-major weights, then the packed forward weights; the row-major copies
+    # are released before the gradient buffers are allocated (config 5: 50 GiB per set of weights)
+    W_in_tp, W_out_tp = torch.empty_like(W_out), torch.empty_like(W_in)
+    lm.locmoe_pack_weights_t(desc, W_in, W_out, W_in_tp, W_out_tp)
     W_in_p, W_out_p = torch.empty_like(W_in), torch.empty_like(W_out)
     lm.locmoe_pack_weights(desc, W_in, W_out, W_in_p, W_out_p)
-    W_in_tp, W_out_tp = torch.empty_like(W_in_t), torch.empty_like(W_out_t)
-    lm.locmoe_pack_weights(desc, W_out_t, W_in_t, W_out_tp, W_in_tp)
     torch.cuda.synchronize()
-    del W_in, W_out, W_in_t, W_out_t
+    del W_in, W_out
+    torch.cuda.empty_cache()
     desc.w_packed = 1
     b, gb = lm.alloc_buffers(desc), lm.alloc_grad_buffers(desc)
+    for t in (b.H, b.out, b.y, gb.Z, gb.dout, gb.dZ, gb.dsend, gb.dx, gb.dW_in, gb.dW_out, gb.dw, gb.dg):
+        t.fill_(float("nan"))                 # a row or tile that a kernel skips cannot pass for a result
     x_dev, dy_dev, home_dev = hz.to_device(x, c.dtype), hz.to_device(dy, c.dtype), i32(torch, home)
     lm.forward_train(desc, x_dev, home_dev, None, W_in_p, W_out_p, b, gb)
     lm.backward(desc, dy_dev, home_dev, None, W_in_tp, W_out_tp, b, gb)
     torch.cuda.synchronize()
+    for name in ("dx", "dW_in", "dW_out", "dw", "dg"):          # every element of these is written
+        assert not bool(torch.isnan(getattr(gb, name)).any()), name
+    for name in ("Z", "dout", "dZ", "dsend"):                   # rows below K written, the rest untouched
+        t = getattr(gb, name)
+        assert not bool(torch.isnan(t[:K]).any()), name
+        assert bool(torch.isnan(t[K:]).all()), name
     say(f"      GPU forward + backward done ({time.time() - t0:.1f}s)")
     assert np.array_equal(b.eid.cpu().numpy(), eid)
     assert np.array_equal(b.slot.cpu().numpy(), s["slot"])
@@ -301,8 +310,9 @@ def run_backward_big(env, c, C):
     assert np.all(np.abs(dg_rows.sum(axis=1)) <= 1e-5 * np.abs(dg_rows).sum(axis=1) + 1e-12)
     # an expert's weight gradient is zero exactly when it kept no rows
     kept_dev = b.kept.cpu().numpy()
-    nz_in = gb.dW_in.float().abs().amax(dim=(1, 2)).cpu().numpy() > 0
-    assert np.array_equal(nz_in, kept_dev > 0)
+    for grad in (gb.dW_in, gb.dW_out):      # expert by expert: the tensors are tens of GiB at the largest shape
+        nz = np.array([bool((grad[e] != 0).any()) for e in range(c.E)])
+        assert np.array_equal(nz, kept_dev > 0)
 
 
 def test_backward_bitwise_repeatable(env):
@@ -367,6 +377,13 @@ def test_backward_expert_count_limits(env):
 
 def test_backward_config4_full_size(env):
     c = wl.CONFIGS[4]
+    run_backward_big(env, c, c.C)
+
+
+def test_backward_config5_full_size(env):
+    """The largest configuration (128 experts, four of them hot, d = 5120): 16 segments per tile queue in the data
+    gradients, 20 x 80 output tiles per expert in the weight gradients."""
+    c = wl.CONFIGS[5]
     run_backward_big(env, c, c.C)
 
 
