@@ -141,6 +141,21 @@ int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int32_t* eid, 
                     int32_t* buf_expert, int32_t* row_token, void* send, void* ws, size_t ws_bytes,
                     void* stream);
 
+/* locmoe_dispatch for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels and the same results, bit for bit, with the scratch
+ * (the per-block expert counts, ceil(T/1024) * E int32) in a static device array inside the library instead of a
+ * caller workspace.  Limit: ceil(T/1024) * E <= LOCMOE_DISPATCH_STATIC_MAX_COUNTS (1 MiB of counts), else
+ * LOCMOE_ERR_WORKSPACE.  The call allocates nothing and frees nothing.  The array's device address is looked up
+ * once per device, on the first call made with that device current (make that call outside a graph capture);
+ * LOCMOE_ERR_HIP if the lookup fails.  Every call on a device uses that device's one array: calls that overlap
+ * on one device (other streams, other threads) race and must not be made; calls on one stream are ordered.
+ * Nothing in the array has to be zero on entry (every count is written before it is read), and its contents
+ * after a call are unspecified.  All other arguments, outputs and errors as locmoe_dispatch. */
+#define LOCMOE_DISPATCH_STATIC_MAX_COUNTS 262144
+int locmoe_dispatch_static(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n,
+                           int32_t* pos, int32_t* slot, int32_t* kept, int32_t* seg_off, int32_t* node_off,
+                           int32_t* buf_expert, int32_t* row_token, void* send, void* stream);
+
 /* Expert FFN of Eq. 1 as a grouped GEMM over the send buffer's segments:
  *   out[r,:] = W_out[e] . GeLU(W_in[e] . send[r,:]) for r in segment of e = buf_expert[rank],
  *   GeLU(v) = v*Phi(v) (erf form), no biases.  bf16 MFMA with fp32 accumulation; the

@@ -6,10 +6,32 @@
 //   3. dispatch_copy_kernel   send[r,:] = x[row_token[r],:] for r < K, 16-byte vectors
 // Integer-only; LDS integer atomics appear only where the result does not depend on their
 // order, so slots are bit-identical from run to run.
+#include <atomic>
+
 #include "common.h"
 
 namespace locmoe {
 namespace {
+
+// Scratch of locmoe_dispatch_static: the [blocks, E] count matrix lives in this array instead of a caller
+// workspace.  Host code never uses the array's name as an address: static_scratch() asks the runtime for the
+// device address once per device and hands that pointer to the kernels.
+constexpr size_t kStaticScratchBytes = size_t(1) << 20;  // 262 144 counts: blocks of 1024 tokens x experts
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (each device holds its own copy), nullptr if the runtime
+// refuses.  Asked once per device; later calls read the cached pointer.
+void* static_scratch() {
+  static std::atomic<void*> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  void* ptr = cached[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    cached[dev].store(ptr, std::memory_order_release);
+  }
+  return ptr;
+}
 
 constexpr int kDispThreads = 256;
 constexpr int kDispWaves = kDispThreads / kWave;
@@ -299,4 +321,20 @@ extern "C" int locmoe_dispatch(const locmoe_desc* desc, const void* x, const int
   if (!ws || ws_bytes < locmoe_workspace_bytes(desc)) return LOCMOE_ERR_WORKSPACE;
   return dispatch_launch(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_expert, row_token, send,
                          (int32_t*)ws, as_stream(stream));
+}
+
+// For callers that cannot allocate: locmoe_dispatch with the count matrix in the library's static scratch.
+extern "C" int locmoe_dispatch_static(const locmoe_desc* desc, const void* x, const int32_t* eid, const int32_t* e2n,
+                                      int32_t* pos, int32_t* slot, int32_t* kept, int32_t* seg_off,
+                                      int32_t* node_off, int32_t* buf_expert, int32_t* row_token, void* send,
+                                      void* stream) {
+  using namespace locmoe;
+  const int st = dispatch_check(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_expert, row_token, send);
+  if (st != LOCMOE_OK) return st;
+  const size_t counts = (size_t)ceil_div(desc->T, kDispatchTokensPerBlock) * (size_t)desc->E;
+  if (counts * sizeof(int32_t) > kStaticScratchBytes) return LOCMOE_ERR_WORKSPACE;  // beyond the stated maximum
+  void* ptr = static_scratch();
+  if (!ptr) return LOCMOE_ERR_HIP;
+  return dispatch_launch(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_expert, row_token, send,
+                         (int32_t*)ptr, as_stream(stream));
 }

@@ -21,7 +21,7 @@ LOCMOE_F32, LOCMOE_BF16 = 0, 1
 
 EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "locmoe_capacity",
            "locmoe_workspace_bytes", "locmoe_gate", "locmoe_gate_sq", "locmoe_angle_stats", "locmoe_route",
-           "locmoe_dispatch",
+           "locmoe_dispatch", "locmoe_dispatch_static",
            "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine",
            "locmoe_packed_weights_bytes", "locmoe_pack_weights", "locmoe_combine_bwd", "locmoe_route_bwd",
            "locmoe_dispatch_bwd", "locmoe_expert_ffn_in_save", "locmoe_transpose_weights",
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
     L.locmoe_angle_stats.argtypes = [D, P, P, P, I32, I32] + [P] * 7
     L.locmoe_route.argtypes = [D] + [P] * 10 + [SZ, P]
     L.locmoe_dispatch.argtypes = [D] + [P] * 12 + [SZ, P]
+    L.locmoe_dispatch_static.argtypes = [D] + [P] * 12
     L.locmoe_expert_ffn.argtypes = [D] + [P] * 8
     L.locmoe_expert_ffn_in.argtypes = [D] + [P] * 6
     L.locmoe_expert_ffn_out.argtypes = [D] + [P] * 6
@@ -178,6 +179,13 @@ def locmoe_dispatch(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_e
     _check(lib().locmoe_dispatch(C.byref(desc), _ptr(x), _ptr(eid), _ptr(e2n), _ptr(pos), _ptr(slot), _ptr(kept),
                                  _ptr(seg_off), _ptr(node_off), _ptr(buf_expert), _ptr(row_token), _ptr(send),
                                  _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def locmoe_dispatch_static(desc, x, eid, e2n, pos, slot, kept, seg_off, node_off, buf_expert, row_token, send,
+                           stream=None):
+    _check(lib().locmoe_dispatch_static(C.byref(desc), _ptr(x), _ptr(eid), _ptr(e2n), _ptr(pos), _ptr(slot),
+                                        _ptr(kept), _ptr(seg_off), _ptr(node_off), _ptr(buf_expert),
+                                        _ptr(row_token), _ptr(send), _stream(stream)))
 
 
 def locmoe_expert_ffn(desc, send, seg_off, buf_expert, W_in, W_out, H_ws, out, stream=None):

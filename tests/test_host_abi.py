@@ -123,6 +123,10 @@ def test_descriptor_validation_without_gpu():
     assert _status(lm.locmoe_dispatch, odd, p, p, None, p, p, p, p, p, p, p, p, p, 1 << 20, 0) == lm.LOCMOE_ERR_SHAPE
     assert _status(lm.locmoe_dispatch, dsc, p, p, None, p, p, p, p, p, p, p, p, None, 0, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_dispatch, dsc, p, None, None, p, p, p, p, p, p, p, p, p, 1 << 20, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_dispatch_static, odd, p, p, None, p, p, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
+    assert _status(lm.locmoe_dispatch_static, dsc, p, p, None, p, None, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_NULL
+    too_big = lm.make_desc(T=1024 * 257, d=1024, E=1024, N=32, h=8, Cap=4)   # 263 168 counts > the static scratch
+    assert _status(lm.locmoe_dispatch_static, too_big, p, p, None, p, p, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_expert_ffn, dsc, p, p, p, p, None, p, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine_bwd, dsc, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
