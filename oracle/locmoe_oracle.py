@@ -22,6 +22,7 @@ values the paper prints; none is "parity unpinned".
 from __future__ import annotations
 
 import math
+from fractions import Fraction
 
 import numpy as np
 from scipy import special as _sp
@@ -56,8 +57,9 @@ def capacity(T: int, E: int, d: int, cf: float, delta: float) -> int:
     """Rows per expert.  The empirical capacity ceil(b_s c_f / (ep n)) of Section 3.2.3
     becomes ceil(c_f T / E) on one device's share of T tokens; it is floored by the
     Theorem 1 bound (erfc form, the one both sides evaluate with libm) and clamped to
-    [1, T].  c_f = 0 selects the bound alone."""
-    emp = math.ceil(cf * T / E - 1e-12) if cf > 0.0 else 0
+    [1, T].  c_f = 0 selects the bound alone.  The ceiling is the plain one of the printed formula, taken of
+    the exact rational value with c_f read as the decimal number it is written as (1.1 is 11/10)."""
+    emp = math.ceil(Fraction(repr(float(cf))) * T / E) if cf > 0.0 else 0
     b = ec_min(E, d, delta, "erfc")
     bound = T if math.isinf(b) or b >= T else math.ceil(b)
     return int(min(max(emp, bound, 1), T))

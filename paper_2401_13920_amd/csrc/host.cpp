@@ -1,7 +1,9 @@
 // Host-only part of liblocmoe: status strings, descriptor validation, the scalar capacity
 // formulas of Section 3.2.3 (Lemma 3, Theorem 1) and the workspace size.
 #include <atomic>
+#include <charconv>
 #include <cmath>
+#include <cstdlib>
 #include <limits>
 
 #include "common.h"
@@ -74,6 +76,39 @@ double reg_inc_beta(double a, double b, double x) {
 // the probability is tiny.
 double p_delta(int d, double delta) { return reg_inc_beta(0.5 * (d - 1), 0.5, 1.0 - delta * delta); }
 
+// ceil(cf * T / E) for the empirical capacity of Section 3.2.3, with the capacity factor read as the decimal
+// number the caller wrote: the shortest decimal that rounds to the given double (1.1 means 11/10, not the double
+// next to it), and the product and quotient formed exactly in integers, so that the plain ceiling of the paper's
+// formula is taken of the plain value (cf = 1.1, T = 100, E = 10 gives 11; a product that is an integer gives that
+// integer; anything above it, however little, gives the next one).  cf > 0 and finite; the result is clamped to
+// [1, T] here already.
+int ceil_cf_tokens_per_expert(double cf, int T, int E) {
+  const double approx = cf * (double)T / (double)E;
+  if (approx < 0.25) return 1;               // the exact value is below 1 as well
+  if (approx > (double)T + 1.0) return T;    // ... above T as well
+  char buf[64];
+  const auto res = std::to_chars(buf, buf + sizeof buf - 1, cf, std::chars_format::scientific);
+  *res.ptr = 0;
+  // "d.ddde[+-]xx" -> digits D and a power of ten: cf = D * 10^p10
+  unsigned __int128 D = 0;
+  int frac_digits = 0;
+  const char* q = buf;
+  bool after_point = false;
+  for (; *q && *q != 'e'; ++q) {
+    if (*q == '.') { after_point = true; continue; }
+    D = D * 10 + (unsigned)(*q - '0');
+    if (after_point) ++frac_digits;
+  }
+  const int p10 = (*q == 'e' ? std::atoi(q + 1) : 0) - frac_digits;
+  // 0.25 E/T <= cf <= (T+1) E/T bounds p10 to [-27, 13]: every product below fits in 128 bits
+  unsigned __int128 num = D * (unsigned __int128)(unsigned)T, den = (unsigned __int128)(unsigned)E;
+  for (int i = 0; i < p10; ++i) num *= 10;
+  for (int i = 0; i < -p10; ++i) den *= 10;
+  const unsigned __int128 c = (num + den - 1) / den;
+  if (c < 1) return 1;
+  return c > (unsigned __int128)(unsigned)T ? T : (int)c;
+}
+
 }  // namespace
 }  // namespace locmoe
 
@@ -129,7 +164,7 @@ int locmoe_capacity(int32_t T, int32_t E, int32_t d, double cf, double delta, in
   const int st = locmoe_capacity_min(E, d, delta, 1, &bound);
   if (st != LOCMOE_OK) return st;
   double rows = bound >= (double)T ? (double)T : std::ceil(bound);
-  if (cf > 0.0) rows = std::fmax(rows, std::ceil(cf * (double)T / (double)E - 1e-12));
+  if (cf > 0.0) rows = std::fmax(rows, (double)ceil_cf_tokens_per_expert(cf, T, E));
   rows = std::fmin(std::fmax(rows, 1.0), (double)T);
   *C = (int32_t)rows;
   return LOCMOE_OK;

@@ -57,6 +57,18 @@ def test_capacity_min_and_capacity_match_oracle():
                 assert lm.locmoe_capacity(c.T, c.E, c.d, cf, delta) == orc.capacity(c.T, c.E, c.d, cf, delta)
         assert lm.locmoe_capacity(c.T, c.E, c.d, 0.0, c.delta) == c.C
     assert lm.locmoe_capacity(100, 8, 64, 0.0, 0.999) == 100
+    # the empirical capacity is a plain ceiling of the exact product, the capacity factor read as a decimal; the
+    # library forms it in integers from the shortest decimal of the double, the oracle in rational arithmetic
+    assert lm.locmoe_capacity(100, 10, 4096, 1.1, 0.01) == 11
+    assert lm.locmoe_capacity(32768, 32, 4096, math.nextafter(1.25, 2.0), 0.01) == 1281
+    rng = np.random.default_rng(11)
+    for _ in range(3000):
+        T = int(rng.integers(1, 2 ** 31 - 1)) if rng.random() < 0.3 else int(rng.integers(1, 200000))
+        E = int(rng.integers(1, 1025))
+        cf = [round(float(rng.uniform(0.01, 4.0)), int(rng.integers(1, 6))), float(rng.uniform(1e-12, 2000.0)),
+              float(np.nextafter(rng.integers(1, 9) / 4.0, 9.0)), 10.0 ** float(rng.integers(-12, 12))][int(rng.integers(0, 4))]
+        if cf > 0:
+            assert lm.locmoe_capacity(T, E, 4096, cf, 0.01) == orc.capacity(T, E, 4096, cf, 0.01), (T, E, cf)
     assert math.isinf(lm.locmoe_capacity_min(8, 4096, 0.9, 1))
 
 
@@ -128,6 +140,19 @@ def test_descriptor_validation_without_gpu():
     too_big = lm.make_desc(T=1024 * 257, d=1024, E=1024, N=32, h=8, Cap=4)   # 263 168 counts > the static scratch
     assert _status(lm.locmoe_dispatch_static, too_big, p, p, None, p, p, p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_expert_ffn, dsc, p, p, p, p, None, p, p, 0) == lm.LOCMOE_ERR_NULL
+    n_ws = lm.LOCMOE_FFN_WS_BYTES
+    assert _status(lm.locmoe_expert_ffn_ws, dsc, p, p, p, p, p, p, p, None, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_ws, dsc, p, p, p, p, p, p, p, p, n_ws - 1, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_ws, dsc, p, p, p, p, p, p, p, p + 2, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_ws, dsc, p, p, p, p, None, p, p, p, n_ws, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_in_ws, dsc, p, p, p, p, p, None, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_in_ws, dsc, None, p, p, p, p, p, n_ws, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_out_ws, dsc, p, p, p, p, p, p, 0, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_out_ws, bad_packed_desc(lm, good), p, p, p, p, p, p, n_ws, 0) == lm.LOCMOE_ERR_ARG
+    assert _status(lm.locmoe_expert_ffn_in_save_ws, dsc, p, p, p, p, p, None, p, n_ws, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_expert_ffn_in_save_ws, dsc, p, p, p, p, p, p, None, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_dgrad_ws, dsc, p, p, p, p, p, p, p, p, None, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
+    assert _status(lm.locmoe_expert_ffn_dgrad_ws, dsc, p, p, p, p, p, p, p, None, p, n_ws, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine_bwd, dsc, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine_bwd, zero_c_desc(lm, good), p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG

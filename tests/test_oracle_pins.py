@@ -86,6 +86,27 @@ def test_capacity_table():
     assert orc.capacity(100, 8, 64, 1.0, 0.01) == 13       # ceil(100/8)
 
 
+def test_empirical_capacity_is_a_plain_ceiling():
+    """Section 3.2.3's empirical capacity is a plain ceiling: an integer product stays, anything above it, however
+    little, goes to the next integer, and a decimal capacity factor means what it says (1.1 * 100 / 10 is 11 although
+    the double next to 1.1 lies above it).  delta is small enough for the Theorem 1 bound to stay at one row."""
+    cap = lambda T, E, cf: orc.capacity(T, E, 4096, cf, 0.01)
+    assert cap(100, 10, 1.1) == 11                          # 11 exactly; in doubles 1.1*100/10 = 11.000000000000002
+    assert cap(1000, 7, 0.7) == 100                         # 100 exactly; in doubles 100.00000000000001
+    assert cap(32768, 32, 1.25) == 1280                     # an integer product is its own ceiling
+    assert cap(32768, 32, math.nextafter(1.25, 2.0)) == 1281    # 1.2500000000000002 is above it: next integer
+    assert cap(32768, 32, math.nextafter(1.25, 0.0)) == 1280    # 1.2499999999999998 is below it
+    assert cap(30, 10, 1.0 / 3.0) == 1 and cap(60, 10, 1.0 / 3.0) == 2      # 0.3333333333333333 * 3 < 1
+    assert cap(30, 1, 0.1) == 3 and cap(30, 1, 0.3) == 9 and cap(7, 2, 2.0) == 7
+    assert cap(65536, 64, 1e-9) == 1 and cap(65536, 64, 1e9) == 65536          # clamped to [1, T]
+    # brute force over small cases: the smallest integer c with c * E * 10 >= tenths * T
+    for T in (7, 64, 100, 999):
+        for E in (2, 3, 8, 10):           # (with one expert the Theorem 1 bound alone already asks for two rows)
+            for tenths in range(1, 31):
+                want = next(c for c in range(0, 10 * T) if c * E * 10 >= tenths * T)
+                assert cap(T, E, tenths / 10.0) == min(max(want, 1), T), (T, E, tenths)
+
+
 # ------------------------------------------------------------------ gate
 def test_grap_weight_orthogonal_equal_norm():
     for E, d in [(8, 128), (16, 1024), (128, 5120), (3, 21)]:
