@@ -19,11 +19,44 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the two grouped-GEMM kernels at the bench workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (KiB per dispatch; profiles/bench_config4_kernels_and_hbm_counters.txt).  FETCH_SIZE is scaled by 2.0,
-# the factor the same counter needs for a plain 1 GiB copy in the same run; WRITE_SIZE needs none.
-PMC_KIB = {"ffn_in": (4687965.2, 837589.1), "ffn_out": (4881599.9, 210171.2)}
+# HBM bytes per launch of the two grouped-GEMM kernels at the bench workload come from the tracked rocprofv3 summary
+# below (--pmc FETCH_SIZE and WRITE_SIZE, KiB per dispatch).  FETCH_SIZE is scaled by 2.0, the factor the same counter
+# needs for a plain 1 GiB copy in the same run; WRITE_SIZE needs none.  The summary records a hash of the kernel
+# sources it was taken with: when the sources have changed since, `traffic` is reported as null.
+PROFILE = os.path.join(ROOT, "profiles", "bench_config4_kernels_and_hbm_counters.txt")
+KERNEL_SOURCES = ("ffn.hip", "common.h", "gelu_coef.h")
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
+
+
+def kernel_sources_hash() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2401_13920_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic():
+    """{'ffn_in': (fetch KiB, write KiB), 'ffn_out': ...} from the tracked summary, and why not if it cannot be used."""
+    import re
+    try:
+        text = open(PROFILE).read()
+    except OSError:
+        return None, "no profile summary in the tree"
+    m = re.search(r"^# kernel sources sha256/16 .*: ([0-9a-f]{16})", text, re.M)
+    if not m:
+        return None, "the profile summary does not record the kernel sources it was taken with"
+    if m.group(1) != kernel_sources_hash():
+        return None, "the profile summary is older than the kernel sources"
+    out = {}
+    for key, tag in (("ffn_out", "<0>"), ("ffn_in", "<1>")):
+        mm = re.search(r"ffn_gemm_dma_persistent" + re.escape(tag) + r".*FETCH_SIZE=\s*([0-9.]+)\s+WRITE_SIZE=\s*([0-9.]+)", text)
+        if not mm:
+            return None, "the profile summary has no counters for the grouped GEMM"
+        out[key] = (float(mm.group(1)), float(mm.group(2)))
+    return out, None
+
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
@@ -95,17 +128,18 @@ def time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in,
     torch.cuda.synchronize()
     relayout = round(e0.elapsed_time(e1), 3)
     names = ["ffn_in_save", "combine_bwd", "dgrad", "wgrad", "route_bwd", "dispatch_bwd"]
-    acc = {n: 0.0 for n in names}
-    total = 0.0
+    acc = {n: [] for n in names}
+    total = []
     for k in range(reps):
         xs, hs, b = sets[k % len(sets)]
         lm.forward(desc, xs, hs, None, W_in, W_out, b, stream=stream)
         evs = [ev() for _ in range(len(names) + 1)]
         evs[0].record(stream)
-        lm.locmoe_expert_ffn_in_save(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, gb.Z, stream); evs[1].record(stream)
+        lm.locmoe_expert_ffn_in_save_ws(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, gb.Z, b.ffn_ws,
+                                        lm.LOCMOE_FFN_WS_BYTES, stream); evs[1].record(stream)
         lm.locmoe_combine_bwd(desc, dy, b.out, b.slot, b.w, gb.dout, gb.dw, stream); evs[2].record(stream)
-        lm.locmoe_expert_ffn_dgrad(desc, gb.dout, gb.Z, b.seg_off, b.buf_expert, W_out_t, W_in_t, gb.dZ, gb.dsend,
-                                   stream); evs[3].record(stream)
+        lm.locmoe_expert_ffn_dgrad_ws(desc, gb.dout, gb.Z, b.seg_off, b.buf_expert, W_out_t, W_in_t, gb.dZ, gb.dsend,
+                                      b.ffn_ws, lm.LOCMOE_FFN_WS_BYTES, stream); evs[3].record(stream)
         lm.locmoe_expert_ffn_wgrad(desc, b.send, b.H, gb.dout, gb.dZ, b.seg_off, b.buf_expert, gb.dW_in, gb.dW_out,
                                    stream); evs[4].record(stream)
         lm.locmoe_route_bwd(desc, b.g, None, hs, None, b.eid, b.cnt, b.Psum, gb.dw, gb.coef, gb.dg, stream)
@@ -113,11 +147,11 @@ def time_backward(lm, hz, wl, torch, np, c, desc, sets, W_in_rm, W_out_rm, W_in,
         lm.locmoe_dispatch_bwd(desc, gb.dsend, b.slot, gb.dg, gb.dx, stream); evs[6].record(stream)
         torch.cuda.synchronize()
         for i, n in enumerate(names):
-            acc[n] += evs[i].elapsed_time(evs[i + 1])
-        total += evs[1].elapsed_time(evs[6])
-    out = {n: round(acc[n] / reps, 4) for n in names}
+            acc[n].append(evs[i].elapsed_time(evs[i + 1]))
+        total.append(evs[1].elapsed_time(evs[6]))
+    out = {n: round(float(np.median(acc[n])), 4) for n in names}      # medians over the timed iterations
     flops = 2.0 * K * c.d * c.h
-    bwd_ms = total / reps
+    bwd_ms = float(np.median(total))
     return {"ms": out, "backward_ms": round(bwd_ms, 4), "weight_relayout_ms": relayout,
             "dgrad_TFLOPs": round(2 * flops / (out["dgrad"] * 1e-3) / 1e12, 1),
             "wgrad_TFLOPs": round(2 * flops / (out["wgrad"] * 1e-3) / 1e12, 1),
@@ -204,8 +238,9 @@ def main() -> int:
 
     # per-call durations with HIP events on the launch stream, over the same rotating sets
     names = ["gate", "route", "dispatch", "ffn_in", "ffn_out", "combine"]
-    acc = {n: 0.0 for n in names}
+    acc = {n: [] for n in names}
     reps = max(args.steps, 5)
+    nws = lm.LOCMOE_FFN_WS_BYTES
     for k in range(reps):
         xs, hs, b = sets[k % len(sets)]
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
@@ -215,13 +250,15 @@ def main() -> int:
         ev[2].record(stream)
         lm.locmoe_dispatch(desc, xs, b.eid, None, b.pos, b.slot, b.kept, b.seg_off, b.node_off, b.buf_expert,
                            b.row_token, b.send, b.ws, b.ws_bytes, stream); ev[3].record(stream)
-        lm.locmoe_expert_ffn_in(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, stream); ev[4].record(stream)
-        lm.locmoe_expert_ffn_out(desc, b.H, b.seg_off, b.buf_expert, W_out, b.out, stream); ev[5].record(stream)
+        lm.locmoe_expert_ffn_in_ws(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, b.ffn_ws, nws, stream)
+        ev[4].record(stream)
+        lm.locmoe_expert_ffn_out_ws(desc, b.H, b.seg_off, b.buf_expert, W_out, b.out, b.ffn_ws, nws, stream)
+        ev[5].record(stream)
         lm.locmoe_combine(desc, b.out, b.slot, b.w, b.y, stream); ev[6].record(stream)
         torch.cuda.synchronize()
         for i, n in enumerate(names):
-            acc[n] += ev[i].elapsed_time(ev[i + 1])
-    ms = {n: acc[n] / reps for n in names}
+            acc[n].append(ev[i].elapsed_time(ev[i + 1]))
+    ms = {n: float(np.median(acc[n])) for n in names}          # median over the timed iterations
     s = 2 if c.dtype == "bf16" else 4
     alg_bytes = {
         "gate": c.T * c.d * s + c.T * c.E * 4,
@@ -246,7 +283,7 @@ def main() -> int:
     hist = torch.empty(2, c.E, nb, dtype=torch.int32, device="cuda")
     cmin = torch.empty(c.E, dtype=torch.float32, device="cuda")
     dstat = torch.empty(4, dtype=torch.float32, device="cuda")
-    est = {"gate_sq": 0.0, "angle_stats": 0.0}
+    est = {"gate_sq": [], "angle_stats": []}
     for k in range(reps):
         xs, hs, b = sets[k % len(sets)]
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -255,11 +292,11 @@ def main() -> int:
         lm.locmoe_angle_stats(desc, b.g, q_dev, b.eid, 1, nb, None, None, hist[0], hist[1], cmin, dstat, stream)
         ev[2].record(stream)
         torch.cuda.synchronize()
-        est["gate_sq"] += ev[0].elapsed_time(ev[1]); est["angle_stats"] += ev[1].elapsed_time(ev[2])
+        est["gate_sq"].append(ev[0].elapsed_time(ev[1])); est["angle_stats"].append(ev[1].elapsed_time(ev[2]))
     est_bytes = {"gate_sq": c.T * c.d * s + 2 * c.T * c.E * 4, "angle_stats": 2 * c.T * c.E * 4 + 4 * c.T}
     estimator = {"delta_hat": round(float(dstat[0]), 5), "nbins": nb}
     for n in est:
-        t = est[n] / reps
+        t = float(np.median(est[n]))
         estimator[n] = {"ms": round(t, 4), "GB/s": round(est_bytes[n] / (t * 1e-3) / 1e9, 1)}
     # the two GEMMs with every expert at capacity (K = E*C rows, the shape the roofline target of the FFN is
     # stated for): token rows stand in for the send buffer, so the operands have the statistics of real ones
@@ -271,20 +308,24 @@ def main() -> int:
         send_full = sets[0][0][:Kf].contiguous()
         Hf = torch.empty(Kf, c.h, dtype=torch.bfloat16, device="cuda")
         of = torch.empty(Kf, c.d, dtype=send_full.dtype, device="cuda")
-        accf = [0.0, 0.0]
+        accf = [[], []]
+        ws_full = sets[0][2].ffn_ws
         for k in range(reps + 2):
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             ev[0].record(stream)
-            lm.locmoe_expert_ffn_in(desc, send_full, seg_full, be_full, W_in, Hf, stream); ev[1].record(stream)
-            lm.locmoe_expert_ffn_out(desc, Hf, seg_full, be_full, W_out, of, stream); ev[2].record(stream)
+            lm.locmoe_expert_ffn_in_ws(desc, send_full, seg_full, be_full, W_in, Hf, ws_full, nws, stream)
+            ev[1].record(stream)
+            lm.locmoe_expert_ffn_out_ws(desc, Hf, seg_full, be_full, W_out, of, ws_full, nws, stream)
+            ev[2].record(stream)
             torch.cuda.synchronize()
             if k >= 2:
-                accf[0] += ev[0].elapsed_time(ev[1]); accf[1] += ev[1].elapsed_time(ev[2])
+                accf[0].append(ev[0].elapsed_time(ev[1])); accf[1].append(ev[1].elapsed_time(ev[2]))
         ff = 2.0 * Kf * c.d * c.h
-        full = {"K": Kf, "ffn_in_ms": round(accf[0] / reps, 4), "ffn_out_ms": round(accf[1] / reps, 4),
-                "ffn_in_TFLOPs": round(ff / (accf[0] / reps * 1e-3) / 1e12, 1),
-                "ffn_out_TFLOPs": round(ff / (accf[1] / reps * 1e-3) / 1e12, 1),
-                "mfma_frac_both": round(2 * ff / ((accf[0] + accf[1]) / reps * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        t_in, t_out = float(np.median(accf[0])), float(np.median(accf[1]))
+        full = {"K": Kf, "ffn_in_ms": round(t_in, 4), "ffn_out_ms": round(t_out, 4),
+                "ffn_in_TFLOPs": round(ff / (t_in * 1e-3) / 1e12, 1),
+                "ffn_out_TFLOPs": round(ff / (t_out * 1e-3) / 1e12, 1),
+                "mfma_frac_both": round(2 * ff / ((t_in + t_out) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
         del send_full, Hf, of
     backward = None
     if not args.no_backward:
@@ -292,12 +333,18 @@ def main() -> int:
     dom = "ffn_in" if ms["ffn_in"] >= ms["ffn_out"] else "ffn_out"
     achieved = flops / (ms[dom] * 1e-3) / 1e12
     kname = "ffn_gemm_dma_persistent" if desc.w_packed else "ffn_gemm_256"
+    traffic, traffic_note = None, "the tracked counters are for the config-4 bench workload with packed weights"
+    if desc.w_packed and c.cfg == 4 and not args.capacity:
+        kib, traffic_note = profiled_traffic()
+        if kib:
+            traffic = round((kib[dom][0] * FETCH_FACTOR + kib[dom][1] * WRITE_FACTOR) * 1024)
     roofline = {"bound": "mfma", "kernel": f"{kname} ({dom})", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": (round((PMC_KIB[dom][0] * FETCH_FACTOR + PMC_KIB[dom][1] * WRITE_FACTOR) * 1024)
-                            if desc.w_packed and c.cfg == 4 and not args.capacity else None),
-                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE)",
+                "traffic": traffic,
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE, from profiles/)",
                 "flops_per_launch": flops, "ms_per_launch": round(ms[dom], 4)}
+    if traffic is None:
+        roofline["traffic_note"] = traffic_note
 
     result = {
         "metric": "MoE-layer fwd tokens/sec (gate+dispatch+FFN+combine); dispatch GB/s vs HBM peak",

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "locmoe.h"
 
 namespace locmoe {
@@ -138,6 +140,17 @@ int check_desc(const locmoe_desc* d);
 // compute units of the current device (the grid of the persistent kernels), 256 if the query fails; asked once
 // per device
 int cu_count();
+
+// Raises a kernel's dynamic-LDS limit to `bytes`, once per device: `done` (one per kernel) remembers the devices
+// it has been raised on, so that the launch path of later calls holds no runtime call beyond the launch itself.
+inline bool allow_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64;
+  if (known && ((done.load(std::memory_order_relaxed) >> dev) & 1u)) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+  if (known) done.fetch_or(uint64_t(1) << dev, std::memory_order_relaxed);
+  return true;
+}
 
 // route / dispatch scratch layout (see workspace.cpp)
 constexpr int kRouteMaxBlocks = 512;     // upper bound of route blocks (partials per block)

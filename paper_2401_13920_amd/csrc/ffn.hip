@@ -19,6 +19,7 @@
 // row m per accumulator quad and stores them as one 8-byte (bf16) or 16-byte (fp32) vector.
 #include <math.h>
 
+#include <algorithm>
 #include <atomic>
 #include <type_traits>
 
@@ -602,13 +603,12 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma(const uint16_t* __re
   wait_vmcnt<0>();  // the tail prefetches must land before the LDS allocation is released
 }
 
-// Tile queues of the persistent kernel, one set per launch slot: words 0..7 are the XCDs' next queue
-// positions, word 8 counts the work-groups that are done with the queues.  All zero between launches: the
-// last work-group to finish puts them back (a launch that dies half way takes the context with it, so
-// nothing stale can be left for a later launch).  Launches take slots round-robin, so launches that overlap
-// on one device (other streams) use different sets as long as fewer than kSchedSlots are in flight.
-constexpr int kSchedSlots = 64;
-__device__ unsigned int g_tile_queue[kSchedSlots][16];
+// Tile queues of the persistent kernel: 9 words of caller memory per launch.  Words 0..7 are the XCDs' next
+// queue positions, word 8 counts the work-groups that are done with the queues.  All zero between launches:
+// the caller hands them over zeroed once, and the last work-group of every launch puts them back.  The library
+// keeps no queue of its own: entry points without a workspace argument run the same kernel with a fixed
+// round-robin assignment of tiles instead (no claims, no state).
+constexpr int kQueueWords = 16;  // one 64-byte set per launch
 
 // A work-group is done with the queues (its last claim has returned); the last one of the grid clears them.
 __device__ __forceinline__ void leave_queues(unsigned int* queue, unsigned groups) {
@@ -643,7 +643,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
                                                                        const int32_t* __restrict__ seg_off,
                                                                        const int32_t* __restrict__ buf_expert,
                                                                        int Kdim, int Ndim, int NT, int E,
-                                                                       unsigned launch_id) {
+                                                                       unsigned int* queue) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -683,10 +683,10 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
   }
   const int total = __builtin_amdgcn_readfirstlane(__shfl(tab_cum, 63, 64));  // lanes past nloc carry the total
   __syncthreads();  // everybody has read the tables before the pipeline overwrites this memory
-  unsigned int* queue = g_tile_queue[launch_id % kSchedSlots];
-  const bool dynamic = stride < total;  // else every tile of this XCD is somebody's first
+  const bool multi = stride < total;     // else every tile of this XCD is somebody's first
+  const bool dynamic = multi && queue;   // tiles beyond the first are claimed from the queue, else taken round-robin
   if (lb >= total) {
-    if (tid == 0) leave_queues(queue, gridDim.x);
+    if (queue && tid == 0) leave_queues(queue, gridDim.x);
     return;
   }
 
@@ -706,7 +706,8 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     const int span = ((rows + mtc - 1) / mtc + 15) & ~15;
     return make_tile(A, Wp, seg0, rows, span, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim);
   };
-  int claimed = 0;
+  // `claimed`: the next tile of this work-group is number stride + claimed of the XCD's list
+  int claimed = lb;
   if (dynamic && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);  // the tile after the first
   DmaTile cur = tile_at(lb);
   const DmaLane ln = make_lane(Kdim, wave, lane);
@@ -719,18 +720,18 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     volatile int* mailbox = (volatile int*)(smem + kWRing + wfree * kWSlotBytes);
     if (tid == 0) *mailbox = claimed;
     __syncthreads();
-    const int jn = dynamic ? stride + __builtin_amdgcn_readfirstlane(*mailbox) : total;
+    const int jn = multi ? stride + __builtin_amdgcn_readfirstlane(*mailbox) : total;
     __syncthreads();
     const bool more = jn < total;
     const DmaTile nxt = more ? tile_at(jn) : tail_alias(cur, KD);
     dma_tile_any<EPI>(cur, nxt, ln, ring, Cout, aux, lds0, KD, lane, wave, Ndim, [&] {
-      if (more && tid == 0) claimed = (int)atomicAdd(&queue[xcd], 1u);
+      if (more && tid == 0) claimed = dynamic ? (int)atomicAdd(&queue[xcd], 1u) : jn;
     });
     wait_vmcnt<0>();  // this tile's stores and the prefetches for the next (or the tail's) have all retired
     if (!more) break;
     cur = nxt;
   }
-  if (tid == 0) leave_queues(queue, gridDim.x);
+  if (queue && tid == 0) leave_queues(queue, gridDim.x);
 }
 
 // Weight packing (one-time): block (e, nt, kt) of 16 KiB is the LDS image of W[e][nt*256 .. +256][kt*32 .. +32]:
@@ -796,32 +797,24 @@ __global__ __launch_bounds__(256) void transpose_pack_kernel(const uint16_t* __r
   }
 }
 
-// names a launch's tile queues; one sequence for every instantiation of the kernel
-inline unsigned next_launch_id() {
-  static std::atomic<unsigned> launches{0};
-  return launches.fetch_add(1u) + 1u;
-}
-
 template <int EPI>
 int launch_dma(const void* A, const void* Wp, void* C, void* aux, const int32_t* seg_off, const int32_t* buf_expert, int E,
-               int rows_max, int Kdim, int Ndim, hipStream_t st) {
+               int rows_max, int Kdim, int Ndim, unsigned int* queue, hipStream_t st) {
   const int MT = ceil_div(rows_max, kBM), NT = Ndim / kBN;
   const long long total = (long long)E * MT * NT;
   if (total > 0x7FFFFFFFLL) return LOCMOE_ERR_SHAPE;
+  static std::atomic<uint64_t> lds_allowed[2];  // per kernel of this instantiation: devices whose LDS limit is raised
   if (E % 8 == 0 && E <= 512) {
     auto kern = ffn_gemm_dma_persistent<EPI>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
-      return LOCMOE_ERR_HIP;
+    if (!allow_lds((const void*)kern, kDmaSmem, lds_allowed[0])) return LOCMOE_ERR_HIP;
     // one work-group per compute unit (160 KiB of LDS each), a multiple of 8 so that every XCD gets as many
     const long long groups = std::min<long long>((cu_count() / 8) * 8, (total + 7) / 8 * 8);
-    const unsigned launch_id = next_launch_id();
     hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
-                       (const uint16_t*)Wp, (uint16_t*)C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, NT, E, launch_id);
+                       (const uint16_t*)Wp, (uint16_t*)C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, NT, E, queue);
     return launch_status();
   }
   auto kern = ffn_gemm_dma<EPI>;
-  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDmaSmem) != hipSuccess)
-    return LOCMOE_ERR_HIP;
+  if (!allow_lds((const void*)kern, kDmaSmem, lds_allowed[1])) return LOCMOE_ERR_HIP;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
                      (const uint16_t*)Wp, (uint16_t*)C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, MT, NT);
   return launch_status();
@@ -871,9 +864,8 @@ int launch_gemm(const void* A, const void* W, void* C, void* aux, const int32_t*
     const long long total = (long long)E * MT * NT;
     if (total <= 0x7FFFFFFFLL) {
       auto kern = ffn_gemm_256<EPI, OUT_F32, 1>;
-      if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kFastSmem) !=
-          hipSuccess)
-        return LOCMOE_ERR_HIP;
+      static std::atomic<uint64_t> lds_allowed;
+      if (!allow_lds((const void*)kern, kFastSmem, lds_allowed)) return LOCMOE_ERR_HIP;
       hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(kFastThreads), kFastSmem, st, (const uint16_t*)A,
                          (const uint16_t*)W, C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, MT, NT, (int)total);
       return launch_status();
@@ -893,14 +885,15 @@ namespace locmoe {
 namespace {
 
 // C[rows, h] = epilogue(A[rows, d] . W[h, d]^T): the first GEMM of Eq. 1 and, with the transposed W_out in
-// place of W_in, the first GEMM of its backward
+// place of W_in, the first GEMM of its backward.  `queue`: 9 zeroed words of caller memory for the tile claims of
+// the packed-weight kernel, or nullptr (fixed tile assignment).
 template <int EPI>
 int gemm_d_to_h(const locmoe_desc* desc, const void* A, const int32_t* seg_off, const int32_t* buf_expert,
-                const void* W, void* Cbf16, void* aux, void* stream) {
+                const void* W, void* Cbf16, void* aux, unsigned int* queue, void* stream) {
   const int rows_max = desc->C < desc->T ? desc->C : desc->T;  // kept[e] <= min(C, T)
   if (desc->w_packed) {
     if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
-    return launch_dma<EPI>(A, W, Cbf16, aux, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h,
+    return launch_dma<EPI>(A, W, Cbf16, aux, seg_off, buf_expert, desc->E, rows_max, desc->d, desc->h, queue,
                            as_stream(stream));
   }
   if (desc->x_dtype == LOCMOE_F32)
@@ -913,11 +906,11 @@ int gemm_d_to_h(const locmoe_desc* desc, const void* A, const int32_t* seg_off, 
 // C[rows, d] = A[rows, h] . W[d, h]^T, A bf16, C of the storage type: the second GEMM of Eq. 1 and, with the
 // transposed W_in in place of W_out, the second GEMM of its backward
 int gemm_h_to_d(const locmoe_desc* desc, const void* A, const int32_t* seg_off, const int32_t* buf_expert,
-                const void* W, void* C, void* stream) {
+                const void* W, void* C, unsigned int* queue, void* stream) {
   const int rows_max = desc->C < desc->T ? desc->C : desc->T;
   if (desc->w_packed) {
     if (desc->x_dtype != LOCMOE_BF16 || !packable(desc)) return LOCMOE_ERR_ARG;
-    return launch_dma<kEpiNone>(A, W, C, nullptr, seg_off, buf_expert, desc->E, rows_max, desc->h, desc->d,
+    return launch_dma<kEpiNone>(A, W, C, nullptr, seg_off, buf_expert, desc->E, rows_max, desc->h, desc->d, queue,
                                 as_stream(stream));
   }
   if (desc->x_dtype == LOCMOE_F32)
@@ -927,58 +920,122 @@ int gemm_h_to_d(const locmoe_desc* desc, const void* A, const int32_t* seg_off, 
                                              desc->d, as_stream(stream));
 }
 
-}  // namespace
-}  // namespace locmoe
+// The two queue sets of a workspace (first and second GEMM of a call); nullptr when the caller gave none.
+inline unsigned int* queue_set(void* ws, int which) {
+  return ws ? (unsigned int*)ws + which * kQueueWords : nullptr;
+}
+inline bool ws_ok(const void* ws, size_t ws_bytes) {
+  return ws && ws_bytes >= LOCMOE_FFN_WS_BYTES && ((uintptr_t)ws & 3u) == 0;
+}
 
-extern "C" int locmoe_expert_ffn_in(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
-                                    const int32_t* buf_expert, const void* W_in, void* H_ws, void* stream) {
-  using namespace locmoe;
+int ffn_in(const locmoe_desc* desc, const void* send, const int32_t* seg_off, const int32_t* buf_expert,
+           const void* W_in, void* H_ws, void* Z, void* ws, void* stream) {
   if (!desc || !send || !seg_off || !buf_expert || !W_in || !H_ws) return LOCMOE_ERR_NULL;
   const int st = check_desc(desc);
   if (st != LOCMOE_OK) return st;
-  return gemm_d_to_h<kEpiGelu>(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, stream);
+  if (Z) return gemm_d_to_h<kEpiGeluSave>(desc, send, seg_off, buf_expert, W_in, H_ws, Z, queue_set(ws, 0), stream);
+  return gemm_d_to_h<kEpiGelu>(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, queue_set(ws, 0), stream);
+}
+
+int ffn_out(const locmoe_desc* desc, const void* H_ws, const int32_t* seg_off, const int32_t* buf_expert,
+            const void* W_out, void* out, void* ws, void* stream) {
+  if (!desc || !H_ws || !seg_off || !buf_expert || !W_out || !out) return LOCMOE_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  return gemm_h_to_d(desc, H_ws, seg_off, buf_expert, W_out, out, queue_set(ws, 1), stream);
+}
+
+int ffn_dgrad(const locmoe_desc* desc, const void* dout, const void* Z, const int32_t* seg_off,
+              const int32_t* buf_expert, const void* W_out_t, const void* W_in_t, void* dZ, void* dsend, void* ws,
+              void* stream) {
+  if (!desc || !dout || !Z || !seg_off || !buf_expert || !W_out_t || !W_in_t || !dZ || !dsend) return LOCMOE_ERR_NULL;
+  int st = check_desc(desc);
+  if (st != LOCMOE_OK) return st;
+  // dZ = (dout . W_out) * GeLU'(Z): W_out^T is [h,d], the orientation of W_in
+  st = gemm_d_to_h<kEpiGeluGrad>(desc, dout, seg_off, buf_expert, W_out_t, dZ, const_cast<void*>(Z), queue_set(ws, 0),
+                                 stream);
+  if (st != LOCMOE_OK) return st;
+  // dsend = dZ . W_in: W_in^T is [d,h], the orientation of W_out
+  return gemm_h_to_d(desc, dZ, seg_off, buf_expert, W_in_t, dsend, queue_set(ws, 1), stream);
+}
+
+}  // namespace
+}  // namespace locmoe
+
+using namespace locmoe;
+
+// ---- without a workspace: stateless, fixed tile assignment ---------------------------------------------------
+extern "C" int locmoe_expert_ffn_in(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                                    const int32_t* buf_expert, const void* W_in, void* H_ws, void* stream) {
+  return ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, nullptr, stream);
 }
 
 extern "C" int locmoe_expert_ffn_in_save(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
                                          const int32_t* buf_expert, const void* W_in, void* H_ws, void* Z,
                                          void* stream) {
-  using namespace locmoe;
-  if (!desc || !send || !seg_off || !buf_expert || !W_in || !H_ws || !Z) return LOCMOE_ERR_NULL;
-  const int st = check_desc(desc);
-  if (st != LOCMOE_OK) return st;
-  return gemm_d_to_h<kEpiGeluSave>(desc, send, seg_off, buf_expert, W_in, H_ws, Z, stream);
+  if (!Z) return LOCMOE_ERR_NULL;
+  return ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, Z, nullptr, stream);
 }
 
 extern "C" int locmoe_expert_ffn_out(const locmoe_desc* desc, const void* H_ws, const int32_t* seg_off,
                                      const int32_t* buf_expert, const void* W_out, void* out, void* stream) {
-  using namespace locmoe;
-  if (!desc || !H_ws || !seg_off || !buf_expert || !W_out || !out) return LOCMOE_ERR_NULL;
-  const int st = check_desc(desc);
-  if (st != LOCMOE_OK) return st;
-  return gemm_h_to_d(desc, H_ws, seg_off, buf_expert, W_out, out, stream);
+  return ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, nullptr, stream);
 }
 
 extern "C" int locmoe_expert_ffn_dgrad(const locmoe_desc* desc, const void* dout, const void* Z,
                                        const int32_t* seg_off, const int32_t* buf_expert, const void* W_out_t,
                                        const void* W_in_t, void* dZ, void* dsend, void* stream) {
-  using namespace locmoe;
-  if (!desc || !dout || !Z || !seg_off || !buf_expert || !W_out_t || !W_in_t || !dZ || !dsend) return LOCMOE_ERR_NULL;
-  int st = check_desc(desc);
-  if (st != LOCMOE_OK) return st;
-  // dZ = (dout . W_out) * GeLU'(Z): W_out^T is [h,d], the orientation of W_in
-  st = gemm_d_to_h<kEpiGeluGrad>(desc, dout, seg_off, buf_expert, W_out_t, dZ, const_cast<void*>(Z), stream);
-  if (st != LOCMOE_OK) return st;
-  // dsend = dZ . W_in: W_in^T is [d,h], the orientation of W_out
-  return gemm_h_to_d(desc, dZ, seg_off, buf_expert, W_in_t, dsend, stream);
+  return ffn_dgrad(desc, dout, Z, seg_off, buf_expert, W_out_t, W_in_t, dZ, dsend, nullptr, stream);
 }
 
 extern "C" int locmoe_expert_ffn(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
                                  const int32_t* buf_expert, const void* W_in, const void* W_out, void* H_ws,
                                  void* out, void* stream) {
   if (!W_out || !out) return LOCMOE_ERR_NULL;
-  const int st = locmoe_expert_ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, stream);
+  const int st = ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, nullptr, stream);
   if (st != LOCMOE_OK) return st;
-  return locmoe_expert_ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, stream);
+  return ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, nullptr, stream);
+}
+
+// ---- with a caller workspace: the packed-weight kernels claim their tiles from it -----------------------------
+extern "C" int locmoe_expert_ffn_in_ws(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                                       const int32_t* buf_expert, const void* W_in, void* H_ws, void* ws,
+                                       size_t ws_bytes, void* stream) {
+  if (!ws_ok(ws, ws_bytes)) return LOCMOE_ERR_WORKSPACE;
+  return ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, ws, stream);
+}
+
+extern "C" int locmoe_expert_ffn_in_save_ws(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                                            const int32_t* buf_expert, const void* W_in, void* H_ws, void* Z, void* ws,
+                                            size_t ws_bytes, void* stream) {
+  if (!Z) return LOCMOE_ERR_NULL;
+  if (!ws_ok(ws, ws_bytes)) return LOCMOE_ERR_WORKSPACE;
+  return ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, Z, ws, stream);
+}
+
+extern "C" int locmoe_expert_ffn_out_ws(const locmoe_desc* desc, const void* H_ws, const int32_t* seg_off,
+                                        const int32_t* buf_expert, const void* W_out, void* out, void* ws,
+                                        size_t ws_bytes, void* stream) {
+  if (!ws_ok(ws, ws_bytes)) return LOCMOE_ERR_WORKSPACE;
+  return ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, ws, stream);
+}
+
+extern "C" int locmoe_expert_ffn_dgrad_ws(const locmoe_desc* desc, const void* dout, const void* Z,
+                                          const int32_t* seg_off, const int32_t* buf_expert, const void* W_out_t,
+                                          const void* W_in_t, void* dZ, void* dsend, void* ws, size_t ws_bytes,
+                                          void* stream) {
+  if (!ws_ok(ws, ws_bytes)) return LOCMOE_ERR_WORKSPACE;
+  return ffn_dgrad(desc, dout, Z, seg_off, buf_expert, W_out_t, W_in_t, dZ, dsend, ws, stream);
+}
+
+extern "C" int locmoe_expert_ffn_ws(const locmoe_desc* desc, const void* send, const int32_t* seg_off,
+                                    const int32_t* buf_expert, const void* W_in, const void* W_out, void* H_ws,
+                                    void* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!W_out || !out) return LOCMOE_ERR_NULL;
+  if (!ws_ok(ws, ws_bytes)) return LOCMOE_ERR_WORKSPACE;
+  const int st = ffn_in(desc, send, seg_off, buf_expert, W_in, H_ws, nullptr, ws, stream);
+  if (st != LOCMOE_OK) return st;
+  return ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, ws, stream);
 }
 
 extern "C" int locmoe_transpose_weights(const locmoe_desc* desc, const void* W_in, const void* W_out, void* W_in_t,

@@ -337,8 +337,8 @@ int launch_wgrad(const void* P, const void* Q, void* G, const int32_t* seg_off, 
     if (total <= 0x3FFFFFFFLL && span < 0x7FFFFFFFLL) {
       using S = WgShape;
       auto kern = wgrad_dma_kernel;
-      if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kSmem) != hipSuccess)
-        return LOCMOE_ERR_HIP;
+      static std::atomic<uint64_t> lds_allowed;
+      if (!allow_lds((const void*)kern, S::kSmem, lds_allowed)) return LOCMOE_ERR_HIP;
       const size_t chunks = (size_t)Mdim * Ndim / 8;
       hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, E), dim3(256), 0, st, (uint4*)G, seg_off, buf_expert,
                          chunks);

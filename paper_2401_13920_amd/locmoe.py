@@ -25,7 +25,11 @@ EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "loc
            "locmoe_expert_ffn", "locmoe_expert_ffn_in", "locmoe_expert_ffn_out", "locmoe_combine",
            "locmoe_packed_weights_bytes", "locmoe_pack_weights", "locmoe_combine_bwd", "locmoe_route_bwd",
            "locmoe_dispatch_bwd", "locmoe_expert_ffn_in_save", "locmoe_transpose_weights",
-           "locmoe_expert_ffn_dgrad", "locmoe_expert_ffn_wgrad", "locmoe_pack_weights_t")
+           "locmoe_expert_ffn_dgrad", "locmoe_expert_ffn_wgrad", "locmoe_pack_weights_t",
+           "locmoe_expert_ffn_ws", "locmoe_expert_ffn_in_ws", "locmoe_expert_ffn_out_ws",
+           "locmoe_expert_ffn_in_save_ws", "locmoe_expert_ffn_dgrad_ws")
+LOCMOE_FFN_WS_BYTES = 128
+LOCMOE_DISPATCH_STATIC_MAX_COUNTS = 262144
 
 
 class locmoe_desc(C.Structure):
@@ -84,6 +88,11 @@ def lib() -> C.CDLL:
     L.locmoe_pack_weights_t.argtypes = [D] + [P] * 5
     L.locmoe_expert_ffn_dgrad.argtypes = [D] + [P] * 9
     L.locmoe_expert_ffn_wgrad.argtypes = [D] + [P] * 9
+    L.locmoe_expert_ffn_ws.argtypes = [D] + [P] * 8 + [SZ, P]
+    L.locmoe_expert_ffn_in_ws.argtypes = [D] + [P] * 6 + [SZ, P]
+    L.locmoe_expert_ffn_out_ws.argtypes = [D] + [P] * 6 + [SZ, P]
+    L.locmoe_expert_ffn_in_save_ws.argtypes = [D] + [P] * 7 + [SZ, P]
+    L.locmoe_expert_ffn_dgrad_ws.argtypes = [D] + [P] * 9 + [SZ, P]
     L.locmoe_packed_weights_bytes.restype = SZ
     L.locmoe_packed_weights_bytes.argtypes = [D]
     L.locmoe_pack_weights.argtypes = [D] + [P] * 5
@@ -203,6 +212,33 @@ def locmoe_expert_ffn_out(desc, H_ws, seg_off, buf_expert, W_out, out, stream=No
                                        _ptr(out), _stream(stream)))
 
 
+def locmoe_expert_ffn_ws(desc, send, seg_off, buf_expert, W_in, W_out, H_ws, out, ws, ws_bytes, stream=None):
+    _check(lib().locmoe_expert_ffn_ws(C.byref(desc), _ptr(send), _ptr(seg_off), _ptr(buf_expert), _ptr(W_in),
+                                      _ptr(W_out), _ptr(H_ws), _ptr(out), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def locmoe_expert_ffn_in_ws(desc, send, seg_off, buf_expert, W_in, H_ws, ws, ws_bytes, stream=None):
+    _check(lib().locmoe_expert_ffn_in_ws(C.byref(desc), _ptr(send), _ptr(seg_off), _ptr(buf_expert), _ptr(W_in),
+                                         _ptr(H_ws), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def locmoe_expert_ffn_out_ws(desc, H_ws, seg_off, buf_expert, W_out, out, ws, ws_bytes, stream=None):
+    _check(lib().locmoe_expert_ffn_out_ws(C.byref(desc), _ptr(H_ws), _ptr(seg_off), _ptr(buf_expert), _ptr(W_out),
+                                          _ptr(out), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def locmoe_expert_ffn_in_save_ws(desc, send, seg_off, buf_expert, W_in, H_ws, Z, ws, ws_bytes, stream=None):
+    _check(lib().locmoe_expert_ffn_in_save_ws(C.byref(desc), _ptr(send), _ptr(seg_off), _ptr(buf_expert),
+                                              _ptr(W_in), _ptr(H_ws), _ptr(Z), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def locmoe_expert_ffn_dgrad_ws(desc, dout, Z, seg_off, buf_expert, W_out_t, W_in_t, dZ, dsend, ws, ws_bytes,
+                               stream=None):
+    _check(lib().locmoe_expert_ffn_dgrad_ws(C.byref(desc), _ptr(dout), _ptr(Z), _ptr(seg_off), _ptr(buf_expert),
+                                            _ptr(W_out_t), _ptr(W_in_t), _ptr(dZ), _ptr(dsend), _ptr(ws), ws_bytes,
+                                            _stream(stream)))
+
+
 def locmoe_packed_weights_bytes(desc: locmoe_desc) -> int:
     return int(lib().locmoe_packed_weights_bytes(C.byref(desc)))
 
@@ -277,6 +313,7 @@ class Buffers:
     y: object
     ws: object
     ws_bytes: int
+    ffn_ws: object = None      # LOCMOE_FFN_WS_BYTES of zeros: the tile queues of the *_ws expert FFN entry points
 
 
 def alloc_buffers(desc: locmoe_desc, device="cuda") -> Buffers:
@@ -295,7 +332,7 @@ def alloc_buffers(desc: locmoe_desc, device="cuda") -> Buffers:
         row_token=torch.empty(rows, **i32), send=torch.empty(rows, d, dtype=xd, device=device),
         H=torch.empty(rows, h, dtype=torch.bfloat16, device=device), out=torch.empty(rows, d, dtype=xd, device=device),
         y=torch.empty(T, d, dtype=xd, device=device), ws=torch.empty(wsb, dtype=torch.uint8, device=device),
-        ws_bytes=wsb)
+        ws_bytes=wsb, ffn_ws=torch.zeros(LOCMOE_FFN_WS_BYTES, dtype=torch.uint8, device=device))
 
 
 def forward(desc, x, home, e2n, W_in, W_out, b: Buffers, eps=None, stream=None):
@@ -304,7 +341,8 @@ def forward(desc, x, home, e2n, W_in, W_out, b: Buffers, eps=None, stream=None):
     locmoe_route(desc, b.g, eps, home, e2n, b.eid, b.w, b.cnt, b.Psum, b.stats, b.ws, b.ws_bytes, stream)
     locmoe_dispatch(desc, x, b.eid, e2n, b.pos, b.slot, b.kept, b.seg_off, b.node_off, b.buf_expert, b.row_token,
                     b.send, b.ws, b.ws_bytes, stream)
-    locmoe_expert_ffn(desc, b.send, b.seg_off, b.buf_expert, W_in, W_out, b.H, b.out, stream)
+    locmoe_expert_ffn_ws(desc, b.send, b.seg_off, b.buf_expert, W_in, W_out, b.H, b.out, b.ffn_ws,
+                         LOCMOE_FFN_WS_BYTES, stream)
     locmoe_combine(desc, b.out, b.slot, b.w, b.y, stream)
     return b.y
 
@@ -344,8 +382,9 @@ def forward_train(desc, x, home, e2n, W_in, W_out, b: Buffers, gb: GradBuffers, 
     locmoe_route(desc, b.g, eps, home, e2n, b.eid, b.w, b.cnt, b.Psum, b.stats, b.ws, b.ws_bytes, stream)
     locmoe_dispatch(desc, x, b.eid, e2n, b.pos, b.slot, b.kept, b.seg_off, b.node_off, b.buf_expert, b.row_token,
                     b.send, b.ws, b.ws_bytes, stream)
-    locmoe_expert_ffn_in_save(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, gb.Z, stream)
-    locmoe_expert_ffn_out(desc, b.H, b.seg_off, b.buf_expert, W_out, b.out, stream)
+    locmoe_expert_ffn_in_save_ws(desc, b.send, b.seg_off, b.buf_expert, W_in, b.H, gb.Z, b.ffn_ws,
+                                 LOCMOE_FFN_WS_BYTES, stream)
+    locmoe_expert_ffn_out_ws(desc, b.H, b.seg_off, b.buf_expert, W_out, b.out, b.ffn_ws, LOCMOE_FFN_WS_BYTES, stream)
     locmoe_combine(desc, b.out, b.slot, b.w, b.y, stream)
     return b.y
 
@@ -354,7 +393,8 @@ def backward(desc, dy, home, e2n, W_in_t, W_out_t, b: Buffers, gb: GradBuffers, 
     """Enqueues the backward steps on one stream, in reverse order of the forward; W_in_t / W_out_t are the
     transposed weights in the layout desc.w_packed names.  Leaves dx, dW_in, dW_out in gb."""
     locmoe_combine_bwd(desc, dy, b.out, b.slot, b.w, gb.dout, gb.dw, stream)
-    locmoe_expert_ffn_dgrad(desc, gb.dout, gb.Z, b.seg_off, b.buf_expert, W_out_t, W_in_t, gb.dZ, gb.dsend, stream)
+    locmoe_expert_ffn_dgrad_ws(desc, gb.dout, gb.Z, b.seg_off, b.buf_expert, W_out_t, W_in_t, gb.dZ, gb.dsend,
+                               b.ffn_ws, LOCMOE_FFN_WS_BYTES, stream)
     locmoe_expert_ffn_wgrad(desc, b.send, b.H, gb.dout, gb.dZ, b.seg_off, b.buf_expert, gb.dW_in, gb.dW_out, stream)
     locmoe_route_bwd(desc, b.g, eps, home, e2n, b.eid, b.cnt, b.Psum, gb.dw, gb.coef, gb.dg, stream)
     locmoe_dispatch_bwd(desc, gb.dsend, b.slot, gb.dg, gb.dx, stream)

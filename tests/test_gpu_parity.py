@@ -233,9 +233,15 @@ def check_ffn(env, c, desc, b, x, s, K, W_in_dev, W_out_dev, weights):
     if dp is not None:                                                   # same inputs through the packed-weight kernels
         Wi, Wo = pack(env, desc, W_in_dev, W_out_dev)
         poison(b.out, b.H)
-        lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out)
+        lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out)       # fixed tile assignment
         torch.cuda.synchronize()
         compare(b.out, b.H)
+        poison(b.out, b.H)
+        lm.locmoe_expert_ffn_ws(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out, b.ffn_ws,
+                                lm.LOCMOE_FFN_WS_BYTES)                                      # tiles claimed from ws
+        torch.cuda.synchronize()
+        compare(b.out, b.H)
+        assert int(b.ffn_ws.max()) == 0
     return ref
 
 
@@ -413,10 +419,11 @@ def test_whole_path_bitwise_repeatable(env):
             assert cur == ref
 
 
-def test_ffn_tile_queues_across_launches_and_streams(env):
-    """The persistent grouped GEMM keeps its tile queues in device memory, one set per launch slot.  More
-    launches in a row than there are slots, and launches that overlap on two streams, must give the bits of
-    a single launch (which is checked against the oracle first)."""
+def test_ffn_tile_claims_against_fixed_assignment_across_launches_and_streams(env):
+    """The persistent grouped GEMM either takes its tiles in a fixed round-robin order (entry points without a
+    workspace) or claims them from queue words in a caller workspace (*_ws).  Both must give the same bits (the
+    fixed form is checked against the oracle first); a workspace must come back zeroed, so that many launches in
+    a row can share one; launches that overlap on two streams use a workspace each."""
     torch, lm, hz = env
     # 8 experts = one segment per XCD, up to 2 x 32 tiles each for 32 work-groups: tiles are claimed dynamically
     c = wl.small_config(T=3000, d=512, E=8, N=2, h=8192, clusters=4)
@@ -431,21 +438,36 @@ def test_ffn_tile_queues_across_launches_and_streams(env):
     lm.forward(dp, hz.to_device(x, c.dtype), i32(torch, home), None, Wi, Wo, b)
     torch.cuda.synchronize()
     K = int(b.seg_off[-1])
-    ref = b.out[:K].view(torch.int16).cpu().numpy().tobytes()
-    for it in range(70):                                   # more launches than queue slots
-        b.H.zero_(); b.out.zero_()
-        lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out)
+    bits = lambda t: t[:K].view(torch.int16).cpu().numpy().tobytes()
+    poison(b.H, b.out)
+    lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out)          # fixed assignment
+    torch.cuda.synchronize()
+    ref, refH = bits(b.out), bits(b.H)
+    nws = lm.LOCMOE_FFN_WS_BYTES
+    for it in range(70):
+        poison(b.H, b.out)
+        lm.locmoe_expert_ffn_ws(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out, b.ffn_ws, nws)
         torch.cuda.synchronize()
-        assert b.out[:K].view(torch.int16).cpu().numpy().tobytes() == ref, it
+        assert bits(b.out) == ref and bits(b.H) == refH, it
+        assert int(b.ffn_ws.max()) == 0, it                                                   # handed back zeroed
+    # the two halves as separate calls, and the variant that keeps Z
+    Z = torch.empty_like(b.H)
+    poison(b.H, b.out, Z)
+    lm.locmoe_expert_ffn_in_save_ws(dp, b.send, b.seg_off, b.buf_expert, Wi, b.H, Z, b.ffn_ws, nws)
+    lm.locmoe_expert_ffn_out_ws(dp, b.H, b.seg_off, b.buf_expert, Wo, b.out, b.ffn_ws, nws)
+    torch.cuda.synchronize()
+    assert bits(b.out) == ref and bits(b.H) == refH and int(b.ffn_ws.max()) == 0
+    assert_rows_written(Z, K, "Z")
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]   # default priority
     Hs = [torch.zeros_like(b.H) for _ in streams]; outs = [torch.zeros_like(b.out) for _ in streams]
+    wss = [torch.zeros(nws, dtype=torch.uint8, device="cuda") for _ in streams]
     torch.cuda.synchronize()
     for rep in range(3):
-        for st, H, out in zip(streams, Hs, outs):
-            lm.locmoe_expert_ffn(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, H, out, stream=st)
+        for st, H, out, w_ in zip(streams, Hs, outs, wss):
+            lm.locmoe_expert_ffn_ws(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, H, out, w_, nws, stream=st)
         torch.cuda.synchronize()
         for out in outs:
-            assert out[:K].view(torch.int16).cpu().numpy().tobytes() == ref, rep
+            assert bits(out) == ref, rep
             out.zero_()
         torch.cuda.synchronize()
 
@@ -558,7 +580,16 @@ def run_big(env, c, C, with_ffn=True):
     poison(b.out, b.H)
     lm.locmoe_expert_ffn(desc, b.send, b.seg_off, b.buf_expert, W_in, W_out, b.H, b.out)
     torch.cuda.synchronize()
-    whole_segments(b.out, b.H, "packed weights")
+    whole_segments(b.out, b.H, "packed weights, fixed tile assignment")
+    out_fixed = b.out[:K].clone()
+    poison(b.out, b.H)
+    lm.locmoe_expert_ffn_ws(desc, b.send, b.seg_off, b.buf_expert, W_in, W_out, b.H, b.out, b.ffn_ws,
+                            lm.LOCMOE_FFN_WS_BYTES)
+    torch.cuda.synchronize()
+    whole_segments(b.out, b.H, "packed weights, tiles claimed from the workspace")
+    assert torch.equal(b.out[:K].view(torch.int16), out_fixed.view(torch.int16))          # the same bits either way
+    assert int(b.ffn_ws.max()) == 0
+    del out_fixed
     # every row of the buffer: two kernels that share neither tiling nor scheduling, each within the bar of the
     # oracle on the segments above, agree on all K rows (a tile skipped or claimed twice on any expert shows here)
     diff = (b.out[:K].float() - out_rm).norm(dim=1)
