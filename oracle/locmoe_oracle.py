@@ -14,6 +14,8 @@ Every function is a plain definition, in float64 unless stated:
 * capacity              Section 3.2.3: empirical capacity, Lemma 3, Theorem 1
 * expert FFN / combine  Eq. 1
 * token-to-gate angles  Section 3.2.3 (the assumption that defines delta_{i,j}), Section 4.1
+* comparison routers    Section 3.2.1 (the dense layer that GrAP replaces, the switch router's gate), Section 2 and
+                        Section 4 (hash routing without learnable parameters)
 
 Readings where the paper is silent are spelled out at each function.  Every
 function here is pinned by the CPU tests against closed forms, brute force or
@@ -334,3 +336,37 @@ def angle_stats(x: np.ndarray, eid: np.ndarray, E: int, shift: int, nbins: int):
     delta_hat = float(cmin.min()) if T > 0 else 2.0
     return c_self, c_other, hist_self, hist_other, cmin, delta_hat
 
+
+
+# --------------------------------------------------------------------------
+# Comparison routers (Section 2, Section 3.2.1, Section 4)
+# --------------------------------------------------------------------------
+
+def gate_dense_learned(x: np.ndarray, Wg: np.ndarray) -> np.ndarray:
+    """The gate as the dense layer Section 3.2.1 says it usually is, with a learned weight omega [n, d]:
+    g[m, i] = omega_i . x_m (raw value, like :func:`gate`; bias and ReLU belong to :func:`route`).  This is the
+    gate of the switch router the paper compares with; GrAP is the special case omega = Eq. 4's weight."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(Wg, dtype=np.float64).T
+
+
+def mix32(v: np.ndarray) -> np.ndarray:
+    """The 32-bit finalizer of MurmurHash3 (a published, public-domain integer mixer; a bijection of the 32-bit
+    integers): xor-shift 16, times 0x85EBCA6B, xor-shift 13, times 0xC2B2AE35, xor-shift 16, all modulo 2^32."""
+    v = np.asarray(v, dtype=np.uint64) & np.uint64(0xFFFFFFFF)
+    v ^= v >> np.uint64(16)
+    v = (v * np.uint64(0x85EBCA6B)) & np.uint64(0xFFFFFFFF)
+    v ^= v >> np.uint64(13)
+    v = (v * np.uint64(0xC2B2AE35)) & np.uint64(0xFFFFFFFF)
+    v ^= v >> np.uint64(16)
+    return v.astype(np.uint32)
+
+
+def route_hash(keys: np.ndarray, E: int, seed: int = 0):
+    """Hash routing as Section 2 and Section 4 describe the hash router: the expert is a fixed, parameter-free,
+    (near-)uniform function of the token's key (its vocabulary id, or its position when no ids are given), and no
+    feature of the token is computed.  Reading (the paper names no hash function): expert = mix32(key + seed *
+    0x9E3779B9 mod 2^32) mod n.  There is no gating score, so the expert's output enters Eq. 1 with weight 1.
+    Returns eid int32 [T], w float64 [T] (ones), cnt int64 [n]."""
+    k = (np.asarray(keys, dtype=np.int64) + (int(seed) * 0x9E3779B9)) & 0xFFFFFFFF
+    eid = (mix32(k).astype(np.uint64) % np.uint64(E)).astype(np.int32)
+    return eid, np.ones(len(eid), dtype=np.float64), np.bincount(eid, minlength=E)

@@ -90,7 +90,32 @@ __global__ __launch_bounds__(1024) void route_bwd_coef_kernel(const int32_t* __r
   if (tid < N) { s_home[tid] = 0; s_pernode[tid] = 0; }
   __syncthreads();
   if (home) {
-    for (int m = tid; m < T; m += 1024) atomicAdd(&s_home[home[m]], 1);
+    // Tokens per home node.  A wave takes 64 tokens at a time and counts them value by value: the first
+    // uncounted lane's node is broadcast, the lanes that hold the same node are counted with one ballot and
+    // retire, and one lane adds the count to the block's histogram; as many rounds as the 64 tokens have
+    // distinct nodes (a handful), instead of 64 atomic adds onto the same few words.  Integer counts: the
+    // order of the adds does not matter.  Sixteen tokens' loads per lane are in flight at a time.
+    const int lane = tid & 63;
+    constexpr int U = 16;
+    for (int base = (tid >> 6) * 64; base < T; base += 1024 * U) {
+      int hv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int m = base + u * 1024 + lane;
+        hv[u] = m < T ? home[m] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        unsigned long long todo = __ballot(hv[u] >= 0);
+        while (todo) {
+          const int first = __ffsll((long long)todo) - 1;
+          const int node = __shfl(hv[u], first, 64);
+          const unsigned long long same = __ballot(hv[u] == node);
+          if (lane == first) atomicAdd(&s_home[node], __popcll(same));
+          todo &= ~same;
+        }
+      }
+    }
     if (tid < E) atomicAdd(&s_pernode[e2n ? e2n[tid] : tid / (E / N)], 1);
   }
   __syncthreads();

@@ -156,25 +156,44 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
 }
 
 constexpr int kFinThreads = 1024;
+constexpr int kFinWaves = kFinThreads / kWave;
 
-// deterministic tree sum of one double per thread (kFinThreads threads)
-__device__ double block_sum(double v, double* buf) {
-  buf[threadIdx.x] = v;
-  __syncthreads();
-  for (int s = kFinThreads / 2; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) buf[threadIdx.x] += buf[threadIdx.x + s];
-    __syncthreads();
+// Sums (and one maximum) over the block of NQ doubles per thread, in a fixed order: a butterfly inside each wave
+// (lane i adds lane i ^ o for o = 32 .. 1), the sixteen wave results through LDS, added in wave order by every
+// thread.  Two barriers for all NQ quantities together.
+template <int NQ>
+__device__ __forceinline__ void block_sums(double (&v)[NQ], double& vmax, double (*part)[kFinWaves]) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) v[q] += __shfl_xor(v[q], o);
+    vmax = fmax(vmax, __shfl_xor(vmax, o));
   }
-  const double r = buf[0];
+  const int wave = threadIdx.x / kWave;
+  if (threadIdx.x % kWave == 0) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) part[q][wave] = v[q];
+    part[NQ][wave] = vmax;
+  }
   __syncthreads();
-  return r;
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < kFinWaves; ++w) t += part[q][w];
+    v[q] = t;
+  }
+  double m = part[NQ][0];
+#pragma unroll
+  for (int w = 1; w < kFinWaves; ++w) m = fmax(m, part[NQ][w]);
+  vmax = m;
 }
 
 // One block: column sums of the per-block partials, then the scalars of Eq. 5 / Eq. 6.
 __global__ __launch_bounds__(kFinThreads) void route_finalize_kernel(
     void* ws, const int32_t* __restrict__ e2n, int has_home, int32_t* __restrict__ cnt,
     float* __restrict__ Psum, float* __restrict__ stats, int nb, int T, int E, int N, float alpha, float mu) {
-  __shared__ double red[kFinThreads];
+  __shared__ double part[6][kFinWaves];
   __shared__ double dpart[kFinThreads];
   __shared__ int32_t ipart[kFinThreads];
   __shared__ int32_t s_cnt[1024];
@@ -183,17 +202,30 @@ __global__ __launch_bounds__(kFinThreads) void route_finalize_kernel(
   __shared__ int32_t s_pernode[1024];
   RouteWs r = route_ws(ws, E, N);
   const int tid = threadIdx.x;
-  {  // cnt and Psum: thread (rb, e) adds rows rb, rb+R, ... ; then row groups are added in order
+  if (tid < N) { s_home[tid] = 0; s_pernode[tid] = 0; }
+  int local = 0;
+  int32_t hi = 0;
+  {  // cnt and Psum: thread (rb, e) adds rows rb, rb+R, ... (independent loads, a batch of 16 rows in flight
+     // at a time); then the row groups are added in order.  The home-node counts the same way.
     const int R = kFinThreads / E;
     const int e = tid % E, rb = tid / E;
     int32_t ci = 0;
     double ps = 0.0;
     if (rb < R) {
-#pragma unroll 8
+#pragma unroll 16
       for (int b = rb; b < nb; b += R) {
         ci += r.cnt[(size_t)b * E + e];
         ps += (double)r.psum[(size_t)b * E + e];
       }
+    }
+    if (has_home) {
+      const int Rn = kFinThreads / N;
+      const int nu = tid % N, rn = tid / N;
+      if (rn < Rn) {
+#pragma unroll 16
+        for (int b = rn; b < nb; b += Rn) hi += r.home[(size_t)b * N + nu];
+      }
+      for (int b = tid; b < nb; b += kFinThreads) local += r.local[b];
     }
     ipart[tid] = ci;
     dpart[tid] = ps;
@@ -207,59 +239,37 @@ __global__ __launch_bounds__(kFinThreads) void route_finalize_kernel(
       cnt[tid] = c;
       Psum[tid] = (float)p;
     }
+    if (has_home) {  // integer adds: any order gives the same counts
+      if (hi) atomicAdd(&s_home[tid % N], hi);
+      if (tid < E) atomicAdd(&s_pernode[e2n ? e2n[tid] : tid / (E / N)], 1);
+    }
     __syncthreads();
   }
-  if (tid < N) { s_home[tid] = 0; s_pernode[tid] = 0; }
-  __syncthreads();
-  int local = 0;
-  if (has_home) {
-    const int R = kFinThreads / N;
-    const int nu = tid % N, rb = tid / N;
-    int32_t hi = 0;
-    if (rb < R) {
-#pragma unroll 8
-      for (int b = rb; b < nb; b += R) hi += r.home[(size_t)b * N + nu];
-    }
-    if (rb < R && hi) atomicAdd(&s_home[nu], hi);
-    if (tid < E) atomicAdd(&s_pernode[e2n ? e2n[tid] : tid / (E / N)], 1);
-    for (int b = tid; b < nb; b += kFinThreads) local += r.local[b];
-  }
-  __syncthreads();
   // Eq. 5: L_aux = alpha * n * sum_i f_i P_i
-  double fp = 0.0, klh = 0.0, kls = 0.0, mx = 0.0, empty = 0.0;
+  double q[5] = {0.0, 0.0, 0.0, (double)local, 0.0};  // f P, KL(f || D_l), KL(P || D_l) terms, local tokens, empty experts
+  double mx = 0.0;
   if (tid < E) {
     const double f = (double)s_cnt[tid] / T, P = s_P[tid] / T;
-    fp = f * P;
+    q[0] = f * P;
     mx = (double)s_cnt[tid];
-    empty = s_cnt[tid] == 0 ? 1.0 : 0.0;
+    q[4] = s_cnt[tid] == 0 ? 1.0 : 0.0;
     if (has_home) {
       // Eq. 6 over experts: D_l[i] = T_node(i) / (T * experts on node(i))
       const int nu = e2n ? e2n[tid] : tid / (E / N);
       const double Dl = (double)s_home[nu] / ((double)T * (double)s_pernode[nu]);
-      if (f > 0.0) klh = Dl > 0.0 ? f * log(f / Dl) : INFINITY;
-      if (P > 0.0) kls = Dl > 0.0 ? P * log(P / Dl) : INFINITY;
+      if (f > 0.0) q[1] = Dl > 0.0 ? f * log(f / Dl) : INFINITY;
+      if (P > 0.0) q[2] = Dl > 0.0 ? P * log(P / Dl) : INFINITY;
     }
   }
-  const double sfp = block_sum(fp, red);
-  const double sklh = block_sum(klh, red);
-  const double skls = block_sum(kls, red);
-  const double sloc = block_sum((double)local, red);
-  const double sempty = block_sum(empty, red);
-  // max count
-  red[tid] = mx;
-  __syncthreads();
-  for (int s = kFinThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) red[tid] = fmax(red[tid], red[tid + s]);
-    __syncthreads();
-  }
+  block_sums<5>(q, mx, part);
   if (tid == 0) {
-    stats[0] = (float)((double)alpha * E * sfp);
-    stats[1] = (float)sklh;
-    stats[2] = (float)skls;
-    stats[3] = (float)((double)mu * sklh);
-    stats[4] = (float)(sloc / T);
-    stats[5] = (float)red[0];
-    stats[6] = (float)sempty;
+    stats[0] = (float)((double)alpha * E * q[0]);
+    stats[1] = (float)q[1];
+    stats[2] = (float)q[2];
+    stats[3] = (float)((double)mu * q[1]);
+    stats[4] = (float)(q[3] / T);
+    stats[5] = (float)mx;
+    stats[6] = (float)q[4];
     stats[7] = 0.f;
   }
 }

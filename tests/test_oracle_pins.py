@@ -441,3 +441,75 @@ def test_angle_stats_by_hand():
     # an expert without tokens keeps the sentinel; every token is counted once per histogram
     _, _, hs3, ho3, cmin3, _ = orc.angle_stats(x, np.zeros(4, dtype=np.int64), 2, 1, 8)
     assert cmin3[1] == 2.0 and hs3.sum() == 4 and ho3.sum() == 4 and hs3[1].sum() == 0
+
+
+# ------------------------------------------------------------------ comparison routers
+def test_dense_learned_gate_contains_grap_and_matches_loops():
+    """Section 3.2.1: the gate is usually a dense layer; GrAP is that layer with Eq. 4's fixed weight."""
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((37, 48))
+    for E in (1, 6, 8, 48):
+        assert np.allclose(orc.gate_dense_learned(x, orc.grap_weight(E, 48)), orc.gate(x, E), rtol=0, atol=1e-13)
+    W = rng.standard_normal((5, 48))
+    g = orc.gate_dense_learned(x, W)
+    for m in (0, 17, 36):
+        for i in range(5):
+            assert g[m, i] == pytest.approx(sum(float(W[i, j]) * float(x[m, j]) for j in range(48)), rel=1e-12, abs=1e-12)
+    sel = np.zeros((3, 48)); sel[0, 7] = 1.0; sel[1, 0] = -2.0; sel[2, 47] = 0.5
+    assert np.array_equal(orc.gate_dense_learned(x, sel), np.stack([x[:, 7], -2.0 * x[:, 0], 0.5 * x[:, 47]], axis=1))
+    # a transposed operand would not even have the right shape; a swapped index shows on a non-square weight
+    assert orc.gate_dense_learned(x, W).shape == (37, 5)
+
+
+def mix32_python(v: int) -> int:
+    v &= 0xFFFFFFFF
+    v ^= v >> 16; v = (v * 0x85EBCA6B) & 0xFFFFFFFF
+    v ^= v >> 13; v = (v * 0xC2B2AE35) & 0xFFFFFFFF
+    v ^= v >> 16
+    return v
+
+
+def unmix32_python(v: int) -> int:
+    """Inverse of the mixer from first principles: an xor-shift by s >= 16 is its own inverse, by 13 needs two
+    more rounds, and an odd multiplier has an inverse modulo 2^32."""
+    v ^= v >> 16
+    v = (v * pow(0xC2B2AE35, -1, 1 << 32)) & 0xFFFFFFFF
+    v ^= (v >> 13) ^ (v >> 26)
+    v = (v * pow(0x85EBCA6B, -1, 1 << 32)) & 0xFFFFFFFF
+    v ^= v >> 16
+    return v
+
+
+def test_hash_router_is_a_fixed_uniform_parameter_free_assignment():
+    """Section 2 / Section 4: the hash router assigns tokens evenly by a fixed function without learnable
+    parameters or token features."""
+    rng = np.random.default_rng(4)
+    keys = rng.integers(0, 2 ** 32, size=2000, dtype=np.uint64)
+    mixed = orc.mix32(keys)
+    assert [int(v) for v in mixed[:200]] == [mix32_python(int(k)) for k in keys[:200]]      # vector form = integer form
+    assert all(unmix32_python(int(v)) == int(k) for v, k in zip(mixed[:500], keys[:500]))    # a bijection: invertible
+    assert int(orc.mix32(np.array([0]))[0]) == 0                                             # fixed point of the mixer
+    assert len(set(int(v) for v in orc.mix32(np.arange(100000)))) == 100000                  # no collisions
+    # avalanche: flipping one input bit flips about half of the output bits
+    flips = [bin(mix32_python(k) ^ mix32_python(k ^ (1 << b))).count("1") for k in range(1, 400) for b in (0, 7, 31)]
+    assert 14.0 < np.mean(flips) < 18.0
+    for E in (3, 16, 64, 128):
+        T = 65536
+        eid, w, cnt = orc.route_hash(np.arange(T), E, seed=5)
+        assert eid.min() >= 0 and eid.max() < E and cnt.sum() == T and np.array_equal(cnt, np.bincount(eid, minlength=E))
+        assert np.all(w == 1.0)
+        chi2 = float(((cnt - T / E) ** 2 / (T / E)).sum())
+        assert chi2 < (E - 1) + 6.0 * np.sqrt(2.0 * (E - 1)) + 10.0                           # even to sampling noise
+        again, _, _ = orc.route_hash(np.arange(T), E, seed=5)
+        assert np.array_equal(eid, again)                                                       # fixed
+        other, _, _ = orc.route_hash(np.arange(T), E, seed=6)
+        assert 0.5 * (1 - 1 / E) < np.mean(other != eid) <= 1.0                                 # the seed re-deals
+        # the definition, token by token
+        for m in (0, 1, 999, T - 1):
+            assert eid[m] == mix32_python((m + 5 * 0x9E3779B9) & 0xFFFFFFFF) % E
+    # the same key always goes to the same expert, wherever it stands in the batch
+    ids = rng.integers(0, 50000, size=4096)
+    eid, _, _ = orc.route_hash(ids, 16, seed=1)
+    first = {}
+    for k, e in zip(ids, eid):
+        assert first.setdefault(int(k), int(e)) == int(e)
