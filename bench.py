@@ -298,6 +298,33 @@ def main() -> int:
     for n in est:
         t = float(np.median(est[n]))
         estimator[n] = {"ms": round(t, 4), "GB/s": round(est_bytes[n] / (t * 1e-3) / 1e9, 1)}
+    # the routers the paper compares with (Section 2, Section 4; not part of the timed step): the dense learned gate
+    # of the switch router in place of GrAP, and hash routing in place of gate + route
+    Wg = hz.to_device(wl.dense_gate_weight(c), c.dtype)
+    keys = i32(wl.token_keys(c))
+    cmp_t = {"gate_dense": [], "route_hash": []}
+    xs, hs, b = sets[0]
+    g_dense = torch.empty_like(b.g); eid_h = torch.empty_like(b.eid); w_h = torch.empty_like(b.w)
+    cnt_h = torch.empty_like(b.cnt)
+    for k in range(reps):
+        xs = sets[k % len(sets)][0]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record(stream)
+        lm.locmoe_gate_dense(desc, xs, Wg, g_dense, stream); ev[1].record(stream)
+        lm.locmoe_route_hash(desc, keys, 1, eid_h, w_h, cnt_h, stream); ev[2].record(stream)
+        torch.cuda.synchronize()
+        cmp_t["gate_dense"].append(ev[0].elapsed_time(ev[1])); cmp_t["route_hash"].append(ev[1].elapsed_time(ev[2]))
+    t_gd, t_rh = float(np.median(cmp_t["gate_dense"])), float(np.median(cmp_t["route_hash"]))
+    gd_bytes = c.T * c.d * s + c.E * c.d * s + c.T * c.E * 4
+    comparators = {
+        "gate_dense": {"ms": round(t_gd, 4), "GB/s": round(gd_bytes / (t_gd * 1e-3) / 1e9, 1),
+                       "hbm_frac": round(gd_bytes / (t_gd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "TFLOP/s": round(2.0 * c.T * c.d * c.E / (t_gd * 1e-3) / 1e12, 1),
+                       "vs_grap_gate_ms": round(ms["gate"], 4)},
+        "route_hash": {"ms": round(t_rh, 4), "GB/s": round(12 * c.T / (t_rh * 1e-3) / 1e9, 1),
+                       "max_count": int(cnt_h.max()), "min_count": int(cnt_h.min())},
+    }
+    del Wg, keys, g_dense
     # the two GEMMs with every expert at capacity (K = E*C rows, the shape the roofline target of the FFN is
     # stated for): token rows stand in for the send buffer, so the operands have the statistics of real ones
     full = None
@@ -359,6 +386,7 @@ def main() -> int:
         "per_step": steps_detail,
         "ffn_every_expert_at_capacity": full,
         "delta_estimator": estimator,
+        "comparators": comparators,
         "backward": backward,
         "roofline": roofline,
     }

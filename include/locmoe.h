@@ -231,6 +231,26 @@ int locmoe_expert_ffn_dgrad_ws(const locmoe_desc* desc, const void* dout, const 
 int locmoe_combine(const locmoe_desc* desc, const void* out, const int32_t* slot, const float* w,
                    void* y, void* stream);
 
+/* ---- The routers the paper compares with (Section 2, Section 4) ------------------------------------------
+ * Only the steps that differ from the LocMoE path; dispatch, expert FFN and combine are shared. */
+
+/* The gate as a dense layer with a learned weight (Section 3.2.1: what the gate usually is, and what GrAP's fixed
+ * weight of Eq. 4 replaces; the switch router's gate): g[m,i] = omega_i . x_m, fp32 accumulation, raw value.
+ * Follow it with locmoe_route (home = NULL) for the top-1 choice, the score of Eq. 3 and the auxiliary loss of
+ * Eq. 5.   x device [T,d] of x_dtype; Wg device [E,d] of x_dtype, row-major; g device [T,E] fp32 (written).
+ * With Wg equal to Eq. 4's weight the result is locmoe_gate's up to the order of the fp32 additions. */
+int locmoe_gate_dense(const locmoe_desc* desc, const void* x, const void* Wg, float* g, void* stream);
+
+/* Hash routing (the hash router of Section 2 / Section 4: a fixed, parameter-free, near-uniform assignment that
+ * reads no feature of the token).  The paper names no hash function; this library's reading:
+ *   eid[m] = mix32(key[m] + seed * 0x9E3779B9 mod 2^32) mod E, mix32 = the 32-bit finalizer of MurmurHash3
+ *   (xor-shift 16, * 0x85EBCA6B, xor-shift 13, * 0xC2B2AE35, xor-shift 16, modulo 2^32);
+ *   w[m] = 1 (there is no gating score: the expert's output enters Eq. 1 unweighted); cnt[e] = #{m: eid[m] = e}.
+ *   key device [T] i32 (the token's vocabulary id, read as unsigned) or NULL (= the token's index m);
+ *   eid device [T] i32, w device [T] fp32, cnt device [E] i32 (all written).  Integer work only. */
+int locmoe_route_hash(const locmoe_desc* desc, const int32_t* key, uint32_t seed, int32_t* eid, float* w,
+                      int32_t* cnt, void* stream);
+
 /* ---- Backward of the same path -------------------------------------------------------------------
  * What is differentiated is the training objective of Section 3.2.2 (the equation after Eq. 6),
  * L_task = L_cross + L_aux + L_loc, as far as it depends on this layer: L_cross arrives as dy = dL_cross/dy,

@@ -367,6 +367,6 @@ def route_hash(keys: np.ndarray, E: int, seed: int = 0):
     feature of the token is computed.  Reading (the paper names no hash function): expert = mix32(key + seed *
     0x9E3779B9 mod 2^32) mod n.  There is no gating score, so the expert's output enters Eq. 1 with weight 1.
     Returns eid int32 [T], w float64 [T] (ones), cnt int64 [n]."""
-    k = (np.asarray(keys, dtype=np.int64) + (int(seed) * 0x9E3779B9)) & 0xFFFFFFFF
+    k = (np.asarray(keys, dtype=np.int64) + ((int(seed) * 0x9E3779B9) & 0xFFFFFFFF)) & 0xFFFFFFFF
     eid = (mix32(k).astype(np.uint64) % np.uint64(E)).astype(np.int32)
     return eid, np.ones(len(eid), dtype=np.float64), np.bincount(eid, minlength=E)

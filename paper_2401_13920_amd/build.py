@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(CSRC, "liblocmoe.so")
-SOURCES = ["host.cpp", "gate.hip", "route.hip", "dispatch.hip", "ffn.hip", "combine.hip", "angles.hip", "backward.hip", "wgrad.hip"]
+SOURCES = ["host.cpp", "gate.hip", "route.hip", "dispatch.hip", "ffn.hip", "combine.hip", "angles.hip", "backward.hip", "wgrad.hip", "comparators.hip"]
 
 # Packed-FP32 instruction selection is switched off for all device code.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", INCLUDE, "-I", CSRC,

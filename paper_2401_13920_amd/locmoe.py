@@ -27,7 +27,7 @@ EXPORTS = ("locmoe_status_string", "locmoe_capacity_min", "locmoe_p_delta", "loc
            "locmoe_dispatch_bwd", "locmoe_expert_ffn_in_save", "locmoe_transpose_weights",
            "locmoe_expert_ffn_dgrad", "locmoe_expert_ffn_wgrad", "locmoe_pack_weights_t",
            "locmoe_expert_ffn_ws", "locmoe_expert_ffn_in_ws", "locmoe_expert_ffn_out_ws",
-           "locmoe_expert_ffn_in_save_ws", "locmoe_expert_ffn_dgrad_ws")
+           "locmoe_expert_ffn_in_save_ws", "locmoe_expert_ffn_dgrad_ws", "locmoe_gate_dense", "locmoe_route_hash")
 LOCMOE_FFN_WS_BYTES = 128
 LOCMOE_DISPATCH_STATIC_MAX_COUNTS = 262144
 
@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
     L.locmoe_expert_ffn_out_ws.argtypes = [D] + [P] * 6 + [SZ, P]
     L.locmoe_expert_ffn_in_save_ws.argtypes = [D] + [P] * 7 + [SZ, P]
     L.locmoe_expert_ffn_dgrad_ws.argtypes = [D] + [P] * 9 + [SZ, P]
+    L.locmoe_gate_dense.argtypes = [D, P, P, P, P]
+    L.locmoe_route_hash.argtypes = [D, P, C.c_uint32, P, P, P, P]
     L.locmoe_packed_weights_bytes.restype = SZ
     L.locmoe_packed_weights_bytes.argtypes = [D]
     L.locmoe_pack_weights.argtypes = [D] + [P] * 5
@@ -169,6 +171,15 @@ def locmoe_gate(desc, x, g, stream=None):
 
 def locmoe_gate_sq(desc, x, g, q, stream=None):
     _check(lib().locmoe_gate_sq(C.byref(desc), _ptr(x), _ptr(g), _ptr(q), _stream(stream)))
+
+
+def locmoe_gate_dense(desc, x, Wg, g, stream=None):
+    _check(lib().locmoe_gate_dense(C.byref(desc), _ptr(x), _ptr(Wg), _ptr(g), _stream(stream)))
+
+
+def locmoe_route_hash(desc, key, seed, eid, w, cnt, stream=None):
+    _check(lib().locmoe_route_hash(C.byref(desc), _ptr(key), int(seed) & 0xFFFFFFFF, _ptr(eid), _ptr(w), _ptr(cnt),
+                                   _stream(stream)))
 
 
 def locmoe_angle_stats(desc, g, q, eid, shift, nbins, c_self, c_other, hist_self, hist_other, cmin, stats,

@@ -185,3 +185,19 @@ def expert_weights(c: Config, e: int):
     """Same as :func:`expert_weights_bits` but as float32 arrays of bf16-representable values."""
     b_in, b_out = expert_weights_bits(c, e)
     return bf16_bits_to_f32(b_in), bf16_bits_to_f32(b_out)
+
+
+def dense_gate_weight(c: Config) -> np.ndarray:
+    """A learned dense gate weight omega [E, d] for the switch-router comparison: iid N(0, 1/d) (so that the
+    gating values of unit-variance features have unit scale), float32 rounded to the storage dtype."""
+    w = _rng(c.cfg, 5).standard_normal((c.E, c.d), dtype=np.float32)
+    w *= np.float32(1.0 / np.sqrt(c.d))
+    return round_to_storage(w, c.dtype)
+
+
+def token_keys(c: Config, T: int | None = None, vocab: int = 50000) -> np.ndarray:
+    """Vocabulary ids for the hash-router comparison: Zipf-like (frequent ids are much more common, as in text),
+    int32 in [0, vocab)."""
+    T = c.T if T is None else T
+    u = _rng(c.cfg, 6).random(T)
+    return np.minimum((vocab ** u - 1.0).astype(np.int64), vocab - 1).astype(np.int32)

@@ -153,6 +153,10 @@ def test_descriptor_validation_without_gpu():
     assert _status(lm.locmoe_expert_ffn_in_save_ws, dsc, p, p, p, p, p, p, None, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_expert_ffn_dgrad_ws, dsc, p, p, p, p, p, p, p, p, None, n_ws, 0) == lm.LOCMOE_ERR_WORKSPACE
     assert _status(lm.locmoe_expert_ffn_dgrad_ws, dsc, p, p, p, p, p, p, p, None, p, n_ws, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_gate_dense, dsc, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_gate_dense, lm.make_desc(**dict(good, d=60)), p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
+    assert _status(lm.locmoe_route_hash, dsc, None, 3, p, None, p, 0) == lm.LOCMOE_ERR_NULL
+    assert _status(lm.locmoe_route_hash, lm.make_desc(**dict(good, E=0)), None, 3, p, p, p, 0) == lm.LOCMOE_ERR_SHAPE
     assert _status(lm.locmoe_combine, dsc, p, p, None, p, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine_bwd, dsc, p, p, p, p, p, None, 0) == lm.LOCMOE_ERR_NULL
     assert _status(lm.locmoe_combine_bwd, zero_c_desc(lm, good), p, p, p, p, p, p, 0) == lm.LOCMOE_ERR_ARG

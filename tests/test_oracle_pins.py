@@ -507,6 +507,10 @@ def test_hash_router_is_a_fixed_uniform_parameter_free_assignment():
         # the definition, token by token
         for m in (0, 1, 999, T - 1):
             assert eid[m] == mix32_python((m + 5 * 0x9E3779B9) & 0xFFFFFFFF) % E
+    # negative ids are read as unsigned, and the largest seed wraps modulo 2^32 like any other
+    eid, _, _ = orc.route_hash(np.array([-1, -25000, 5]), 7, seed=0xFFFFFFFF)
+    assert [int(e) for e in eid] == [mix32_python(((k & 0xFFFFFFFF) + 0xFFFFFFFF * 0x9E3779B9) & 0xFFFFFFFF) % 7
+                                     for k in (-1, -25000, 5)]
     # the same key always goes to the same expert, wherever it stands in the batch
     ids = rng.integers(0, 50000, size=4096)
     eid, _, _ = orc.route_hash(ids, 16, seed=1)
