@@ -8,6 +8,8 @@
 // results, bitwise repeatable.
 #include <math.h>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace locmoe {
@@ -76,9 +78,25 @@ __global__ __launch_bounds__(kBwdThreads) void combine_bwd_kernel(const uint4* _
   if (l == 0) dw[m] = acc;
 }
 
-// One block: tokens per home node, experts per node, then the per-expert coefficient that every token's
+// Tokens per home node, first pass: every block counts its share of the tokens in LDS (integer atomics: the
+// order does not matter) and writes one row of a [blocks, N] matrix.  The matrix lives in the front of dg, which
+// locmoe_route_bwd writes only afterwards (no entry point of the backward takes a workspace).
+constexpr int kHomeThreads = 256;
+__global__ __launch_bounds__(kHomeThreads) void route_bwd_home_kernel(const int32_t* __restrict__ home,
+                                                                      int32_t* __restrict__ part, int T, int N,
+                                                                      int per_block) {
+  extern __shared__ int32_t hist[];
+  for (int i = threadIdx.x; i < N; i += kHomeThreads) hist[i] = 0;
+  __syncthreads();
+  const int m0 = blockIdx.x * per_block, m1 = min(T, m0 + per_block);
+  for (int m = m0 + threadIdx.x; m < m1; m += kHomeThreads) atomicAdd(&hist[home[m]], 1);
+  __syncthreads();
+  for (int i = threadIdx.x; i < N; i += kHomeThreads) part[(size_t)blockIdx.x * N + i] = hist[i];
+}
+
+// One block: column sums of that matrix, experts per node, then the per-expert coefficient that every token's
 // dp receives: alpha n f_i / T (Eq. 5, f fixed) + mu (ln(P_i / D_l[i]) + 1) / T (Eq. 6 through P).
-__global__ __launch_bounds__(1024) void route_bwd_coef_kernel(const int32_t* __restrict__ home,
+__global__ __launch_bounds__(1024) void route_bwd_coef_kernel(const int32_t* __restrict__ part, int nblk,
                                                               const int32_t* __restrict__ e2n,
                                                               const int32_t* __restrict__ cnt,
                                                               const float* __restrict__ Psum,
@@ -89,39 +107,30 @@ __global__ __launch_bounds__(1024) void route_bwd_coef_kernel(const int32_t* __r
   const int tid = threadIdx.x;
   if (tid < N) { s_home[tid] = 0; s_pernode[tid] = 0; }
   __syncthreads();
-  if (home) {
-    // Tokens per home node.  A wave takes 64 tokens at a time and counts them value by value: the first
-    // uncounted lane's node is broadcast, the lanes that hold the same node are counted with one ballot and
-    // retire, and one lane adds the count to the block's histogram; as many rounds as the 64 tokens have
-    // distinct nodes (a handful), instead of 64 atomic adds onto the same few words.  Integer counts: the
-    // order of the adds does not matter.  Sixteen tokens' loads per lane are in flight at a time.
-    const int lane = tid & 63;
-    constexpr int U = 16;
-    for (int base = (tid >> 6) * 64; base < T; base += 1024 * U) {
-      int hv[U];
+  if (part) {
+    // thread (rg, nu) adds rows rg, rg + R, ... of column nu: eight unconditional loads at a time (rows past the
+    // end re-read row rg and are not added), so that a batch is in flight together
+    const int R = 1024 / N, nu = tid % N, rg = tid / N;
+    if (rg < R && rg < nblk) {
+      int32_t sum = 0;
+      for (int q0 = rg; q0 < nblk; q0 += 8 * R) {
+        int32_t v[8];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int m = base + u * 1024 + lane;
-        hv[u] = m < T ? home[m] : -1;
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        unsigned long long todo = __ballot(hv[u] >= 0);
-        while (todo) {
-          const int first = __ffsll((long long)todo) - 1;
-          const int node = __shfl(hv[u], first, 64);
-          const unsigned long long same = __ballot(hv[u] == node);
-          if (lane == first) atomicAdd(&s_home[node], __popcll(same));
-          todo &= ~same;
+        for (int u = 0; u < 8; ++u) {
+          const int q = q0 + u * R;
+          v[u] = part[(size_t)(q < nblk ? q : rg) * N + nu];
         }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += (q0 + u * R < nblk) ? v[u] : 0;
       }
+      if (sum) atomicAdd(&s_home[nu], sum);
     }
     if (tid < E) atomicAdd(&s_pernode[e2n ? e2n[tid] : tid / (E / N)], 1);
   }
   __syncthreads();
   if (tid < E) {
     double c = (double)alpha * E * ((double)cnt[tid] / T) / T;
-    if (home && mu != 0.f) {
+    if (part && mu != 0.f) {
       const int nu = e2n ? e2n[tid] : tid / (E / N);
       const double Dl = (double)s_home[nu] / ((double)T * (double)s_pernode[nu]);
       const double P = (double)Psum[tid] / T;
@@ -254,7 +263,21 @@ extern "C" int locmoe_route_bwd(const locmoe_desc* desc, const float* g, const f
   if (!e2n && desc->E % desc->N != 0) return LOCMOE_ERR_SHAPE;
   hipStream_t s = as_stream(stream);
   const int E = desc->E, T = desc->T;
-  hipLaunchKernelGGL(route_bwd_coef_kernel, dim3(1), dim3(1024), 0, s, home, e2n, cnt, Psum, coef, T, E, desc->N,
+  // tokens per home node: partial counts of up to 256 blocks in the front of dg (T E words; N <= E, so a matrix
+  // of at most T rows always fits), summed by the coefficient kernel before dg itself is written
+  const int N = desc->N;
+  int32_t* part = nullptr;
+  int nblk = 0;
+  if (home) {
+    const long long fit = (long long)T * E / N;
+    nblk = (int)std::min<long long>(std::min<long long>(256, ceil_div(T, kHomeThreads)), fit);
+    const int per_block = ceil_div(T, nblk);
+    nblk = ceil_div(T, per_block);
+    part = (int32_t*)dg;
+    hipLaunchKernelGGL(route_bwd_home_kernel, dim3(nblk), dim3(kHomeThreads), (size_t)N * 4, s, home, part, T, N,
+                       per_block);
+  }
+  hipLaunchKernelGGL(route_bwd_coef_kernel, dim3(1), dim3(1024), 0, s, part, nblk, e2n, cnt, Psum, coef, T, E, N,
                      desc->alpha, desc->mu);
   int G = 1;
   while (G < 64 && 2 * G <= E) G *= 2;

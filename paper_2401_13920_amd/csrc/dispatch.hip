@@ -94,12 +94,22 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_slots_kernel(
     for (int e0 = 0; e0 < E; e0 += kDispThreads) {
       const int e = e0 + (R > 1 ? tid % E : tid), rg = R > 1 ? tid / E : 0;
       int before = 0, all = 0;
-      if (e < E && rg < R) {
-#pragma unroll 16
-        for (int q = rg; q < nblocks; q += R) {  // (independent loads: all of an unrolled batch are in flight together)
-          const int c = blockcnt[(size_t)q * E + e];
-          before += q < b ? c : 0;
-          all += c;
+      if (e < E && rg < R && rg < nblocks) {
+        // (unconditional loads - rows past the end re-read row rg and are not added - so that a batch of eight is
+        // in flight at once; with the bound inside the loop every load waited for the one before it)
+        for (int q0 = rg; q0 < nblocks; q0 += 8 * R) {
+          int c[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int q = q0 + u * R;
+            c[u] = blockcnt[(size_t)(q < nblocks ? q : rg) * E + e];
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int q = q0 + u * R;
+            before += q < b ? c[u] : 0;   // (b < nblocks: rows past the end are never before this block)
+            all += q < nblocks ? c[u] : 0;
+          }
         }
       }
       if (R > 1) {

@@ -79,8 +79,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
   const int tok0 = blockIdx.x * tokens_per_block;
   const int tok1 = min(T, tok0 + tokens_per_block);
   // the loads of the next batch of tokens are issued before the current batch is reduced
+  // (the tokens' home nodes come with the batch: fetched where they are used, behind the arg-max, each was a
+  // memory round trip of its own on the critical path)
   float v[kTokPerGroup][EPL], nxt[kTokPerGroup][EPL];
-  auto load_batch = [&](float (&dst)[kTokPerGroup][EPL], int base) {
+  int hv[kTokPerGroup], hnxt[kTokPerGroup];
+  auto load_batch = [&](float (&dst)[kTokPerGroup][EPL], int (&hdst)[kTokPerGroup], int base) {
 #pragma unroll
     for (int t = 0; t < kTokPerGroup; ++t) {
       const int m = base + t * G + grp;
@@ -89,15 +92,18 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
         const int i = j + k * S;
         dst[t][k] = (m < tok1 && i < E) ? g[(size_t)m * E + i] : -INFINITY;
       }
+      hdst[t] = (home && j == 0 && m < tok1) ? home[m] : 0;
     }
   };
-  load_batch(nxt, tok0);
+  load_batch(nxt, hnxt, tok0);
   for (int base = tok0; base < tok1; base += G * kTokPerGroup) {
 #pragma unroll
-    for (int t = 0; t < kTokPerGroup; ++t)
+    for (int t = 0; t < kTokPerGroup; ++t) {
 #pragma unroll
       for (int k = 0; k < EPL; ++k) v[t][k] = nxt[t][k];
-    load_batch(nxt, base + G * kTokPerGroup);
+      hv[t] = hnxt[t];
+    }
+    load_batch(nxt, hnxt, base + G * kTokPerGroup);
 #pragma unroll
     for (int t = 0; t < kTokPerGroup; ++t) {
       const int m = base + t * G + grp;
@@ -129,7 +135,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
           w[m] = inv;  // exp(0) / sum
           atomicAdd(&hist[bi], 1);
           if (home) {
-            const int hn = home[m];
+            const int hn = hv[t];
             atomicAdd(&hhist[hn], 1);
             const int node = e2n ? e2n[bi] : bi / per_node;
             if (node == hn) atomicAdd(local, 1);
@@ -205,28 +211,58 @@ __global__ __launch_bounds__(kFinThreads) void route_finalize_kernel(
   if (tid < N) { s_home[tid] = 0; s_pernode[tid] = 0; }
   int local = 0;
   int32_t hi = 0;
-  {  // cnt and Psum: thread (rb, e) adds rows rb, rb+R, ... (independent loads, a batch of 16 rows in flight
-     // at a time); then the row groups are added in order.  The home-node counts the same way.
+  {  // cnt and Psum: thread (rb, e) adds rows rb, rb+R, ... in order; then the row groups are added in order.
+     // The home-node counts the same way.
     const int R = kFinThreads / E;
     const int e = tid % E, rb = tid / E;
     int32_t ci = 0;
     double ps = 0.0;
-    if (rb < R) {
-#pragma unroll 16
-      for (int b = rb; b < nb; b += R) {
-        ci += r.cnt[(size_t)b * E + e];
-        ps += (double)r.psum[(size_t)b * E + e];
+    // Loads are unconditional (rows past the end re-read the thread's first row and are not added) and all of
+    // a round's loads - counts, probability sums, home counts, locality counts - are issued before the first
+    // is used: the partials were written by other XCDs, every dependent round trip costs microseconds, and with
+    // the bound inside the loop every load waited for the one before it.
+    constexpr int U = 32, UH = 8;
+    const int Rn = kFinThreads / N;
+    const int nu = tid % N, rn = tid / N;
+    const bool cols = rb < R && rb < nb, hcols = has_home && rn < Rn && rn < nb;
+    for (int b0 = 0; b0 < nb; b0 += U * R) {
+      int32_t cv[U];
+      float pv[U];
+      int32_t hvv[UH];
+      if (cols) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int b = b0 + rb + u * R;
+          const size_t at = (size_t)(b < nb ? b : rb) * E + e;
+          cv[u] = r.cnt[at];
+          pv[u] = r.psum[at];
+        }
+      }
+      const bool hround = hcols && b0 == 0;   // the home counts go with the first round (looped below if they are many)
+      if (hround) {
+#pragma unroll
+        for (int u = 0; u < UH; ++u) {
+          const int b = rn + u * Rn;
+          hvv[u] = r.home[(size_t)(b < nb ? b : rn) * N + nu];
+        }
+      }
+      if (has_home && b0 == 0)
+        for (int b = tid; b < nb; b += kFinThreads) local += r.local[b];
+      if (cols) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const bool live = b0 + rb + u * R < nb;
+          ci += live ? cv[u] : 0;
+          ps += live ? (double)pv[u] : 0.0;
+        }
+      }
+      if (hround) {
+#pragma unroll
+        for (int u = 0; u < UH; ++u) hi += (rn + u * Rn < nb) ? hvv[u] : 0;
       }
     }
-    if (has_home) {
-      const int Rn = kFinThreads / N;
-      const int nu = tid % N, rn = tid / N;
-      if (rn < Rn) {
-#pragma unroll 16
-        for (int b = rn; b < nb; b += Rn) hi += r.home[(size_t)b * N + nu];
-      }
-      for (int b = tid; b < nb; b += kFinThreads) local += r.local[b];
-    }
+    if (hcols)  // home counts beyond the first UH rows of this thread (few nodes per thread group: rare)
+      for (int b = rn + UH * Rn; b < nb; b += Rn) hi += r.home[(size_t)b * N + nu];
     ipart[tid] = ci;
     dpart[tid] = ps;
     __syncthreads();
