@@ -531,6 +531,14 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
   ring = DmaRing{wcur, acur};
   __builtin_amdgcn_sched_barrier(0);  // (nothing that reads an accumulator may be scheduled above the wait states)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMAs have written their accumulators
+  // The MFMAs are opaque to the compiler, which therefore adds no wait states of its own, and neither the memory
+  // clobber nor the scheduling barrier orders a register-only accumulator read (v_accvgpr_read, an accumulator
+  // spill) against the statement above: such reads were seen hoisted above it.  An empty statement that "modifies"
+  // every accumulator after the wait states makes each later read depend on a point behind them.
+#pragma unroll
+  for (int ni = 0; ni < 8; ++ni)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) asm volatile("" : "+a"(acc[ni][j]));
   __builtin_amdgcn_sched_barrier(0);
   before_epilogue();
 

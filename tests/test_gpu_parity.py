@@ -367,6 +367,8 @@ def test_tuned_gemm_tiles_with_ragged_segments(env):
     run_full(env, wl.small_config(T=2000, d=768, E=12, N=4, h=256, clusters=3), 400)
     # the shortest K the packed layout allows (four double steps) with three m-tiles per segment
     run_full(env, wl.small_config(T=3000, d=256, E=8, N=2, h=256, clusters=2), 700)
+    # a long contraction (h = 8192) behind wide rows (d = 4096): more tiles on every XCD than it has work-groups
+    run_full(env, wl.small_config(T=6000, d=4096, E=8, N=2, h=8192, clusters=2), 700)
 
 
 def angles_case(env, c, shift, nbins, T=None, zero_rows=(), want_cos=True):
