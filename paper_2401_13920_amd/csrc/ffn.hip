@@ -675,21 +675,30 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
   }
   __syncthreads();
   int tab_seg = 0, tab_cum = 0;  // lane k < nloc: segment of local rank k, tiles of local ranks 0..k
-  {
-    int ntile = 0;
-    if (lane < nloc) {
-      tab_seg = s_tab[lane];
-      const int rows = s_seg[tab_seg + 1] - s_seg[tab_seg];
-      ntile = ((rows + kBM - 1) / kBM) * NT;
-    }
-    tab_cum = ntile;
+  int tab_rows = 0;
+  if (lane < nloc) {
+    tab_seg = s_tab[lane];
+    tab_rows = s_seg[tab_seg + 1] - s_seg[tab_seg];
+  }
+  auto count_tiles = [&](int bm) {  // fills tab_cum for m-tiles of at most bm rows, returns the XCD's tile count
+    tab_cum = ((tab_rows + bm - 1) / bm) * NT;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int up = __shfl_up(tab_cum, o, 64);
       if (lane >= o) tab_cum += up;
     }
+    return __builtin_amdgcn_readfirstlane(__shfl(tab_cum, 63, 64));  // lanes past nloc carry the total
+  };
+  // m-tiles hold at most kBM rows, unless that leaves work-groups of this XCD without a tile (a short tile list:
+  // few experts, narrow outputs): then at most kBM / 2 or kBM / 4 rows, two or four times as many tiles.  A short
+  // tile costs most of a full one (the weight stream is the same), so this pays only for work-groups that would
+  // idle otherwise.  Every output element is still summed by one lane in the same order: same bits.
+  int bm = kBM;
+  int total = count_tiles(bm);
+  if (total > 0 && 2 * total <= stride) {
+    bm = 4 * total <= stride ? kBM / 4 : kBM / 2;
+    total = count_tiles(bm);
   }
-  const int total = __builtin_amdgcn_readfirstlane(__shfl(tab_cum, 63, 64));  // lanes past nloc carry the total
   __syncthreads();  // everybody has read the tables before the pipeline overwrites this memory
   const bool multi = stride < total;     // else every tile of this XCD is somebody's first
   const bool dynamic = multi && queue;   // tiles beyond the first are claimed from the queue, else taken round-robin
@@ -710,7 +719,7 @@ __global__ __launch_bounds__(kDmaThreads) void ffn_gemm_dma_persistent(const uin
     // tile that take equally long stay in step and share the weight stream through L2.  Cut at 256 rows, a
     // short last tile ran ahead of its partner, the stream was fetched twice and the kernel became HBM-bound
     // (272 rows per expert: 3.3 -> 2.45 ms for the second GEMM).
-    const int mtc = (rows + kBM - 1) / kBM;
+    const int mtc = (rows + bm - 1) / bm;
     const int span = ((rows + mtc - 1) / mtc + 15) & ~15;
     return make_tile(A, Wp, seg0, rows, span, within % mtc, within / mtc, buf_expert[r], Kdim, Ndim);
   };
@@ -816,7 +825,8 @@ int launch_dma(const void* A, const void* Wp, void* C, void* aux, const int32_t*
     auto kern = ffn_gemm_dma_persistent<EPI>;
     if (!allow_lds((const void*)kern, kDmaSmem, lds_allowed[0])) return LOCMOE_ERR_HIP;
     // one work-group per compute unit (160 KiB of LDS each), a multiple of 8 so that every XCD gets as many
-    const long long groups = std::min<long long>((cu_count() / 8) * 8, (total + 7) / 8 * 8);
+    // (up to four work-groups per tile of the upper bound: the kernel cuts the m-tiles of a short list finer)
+    const long long groups = std::min<long long>((cu_count() / 8) * 8, (4 * total + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(kDmaThreads), kDmaSmem, st, (const uint16_t*)A,
                        (const uint16_t*)Wp, (uint16_t*)C, (uint16_t*)aux, seg_off, buf_expert, Kdim, Ndim, NT, E, queue);
     return launch_status();
