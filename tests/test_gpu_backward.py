@@ -224,20 +224,35 @@ def test_backward_tuned_tiles_with_ragged_segments(env):
     run_backward_case(env, wl.small_config(T=1500, d=768, E=12, N=4, h=256, clusters=3), 33)
 
 
-def run_backward_big(env, c, C):
+def run_backward_big(env, c, C, repeats=1):
     """A full-size shape in the benchmark's launch configuration (packed weights, persistent kernels):
     two whole experts against the oracle (their dout, dsend, dW_in, dW_out and the dx rows of their tokens),
-    dropped tokens, and properties that hold at any size."""
+    dropped tokens, and properties that hold at any size.  With repeats > 1 the tokens (and their upstream
+    gradients) are c's, repeated that many times on the device: a way to reach token counts whose inputs would
+    take minutes to draw; the oracle sees the repeated sequence like any other."""
+    import dataclasses
     import time
     torch, lm, hz = env
     alpha, mu = wl.ALPHA, wl.MU
     t0 = time.time()
-    x, home = wl.hidden_states(c)
-    dy = wl.upstream_grad(c)
+    xb, homeb = wl.hidden_states(c)
+    dyb = wl.upstream_grad(c)
+    Tb = c.T
+    c = dataclasses.replace(c, T=repeats * Tb)
     T = c.T
+    home = np.tile(homeb, repeats)
+
+    class Rows:                      # row t of the repeated sequence
+        def __init__(self, a):
+            self.a = a
+
+        def __getitem__(self, t):
+            return self.a[np.asarray(t) % Tb]
+
+    x, dy = Rows(xb), Rows(dyb)
     say(f"[bwd big] cfg={c.cfg} T={T} d={c.d} E={c.E} h={c.h} C={C}; inputs {time.time() - t0:.1f}s")
     e2n_full = np.arange(c.E) // (c.E // c.N)
-    g32 = orc.gate(x, c.E).astype(np.float32)
+    g32 = np.tile(orc.gate(xb, c.E).astype(np.float32), (repeats, 1))
     eid, w, p, _ = orc.route(g32)
     st = orc.route_stats(eid, p, home, e2n_full, c.N, alpha, mu)
     s = orc.slots(eid, c.E, C, e2n_full, c.N)
@@ -245,6 +260,11 @@ def run_backward_big(env, c, C):
     kept_cnt = s["kept"]
     order = np.argsort(kept_cnt)
     cand = [int(order[-1]), int(order[len(order) // 2])]          # the fullest expert and a median one
+    if repeats > 1:                                               # ... and the one whose rows come last in the buffers
+        last = max(r for r in range(c.E) if s["seg_off"][r + 1] > s["seg_off"][r])
+        if int(s["buf_expert"][last]) not in cand:
+            cand.append(int(s["buf_expert"][last]))
+        assert int(s["seg_off"][last + 1]) * c.d > 2 ** 31
     W_in, W_out, host_w = hz.upload_weights(c, keep=set(cand), progress=lambda a, n: say(f"      weights {a}/{n}"))
     desc = lm.make_desc(T, c.d, c.E, c.N, c.h, C, c.dtype, True, alpha, mu)
     # packed transposes straight from the row-major weights, then the packed forward weights; the row-major copies
@@ -260,7 +280,9 @@ def run_backward_big(env, c, C):
     b, gb = lm.alloc_buffers(desc), lm.alloc_grad_buffers(desc)
     for t in (b.H, b.out, b.y, gb.Z, gb.dout, gb.dZ, gb.dsend, gb.dx, gb.dW_in, gb.dW_out, gb.dw, gb.dg):
         t.fill_(float("nan"))                 # a row or tile that a kernel skips cannot pass for a result
-    x_dev, dy_dev, home_dev = hz.to_device(x, c.dtype), hz.to_device(dy, c.dtype), i32(torch, home)
+    x_dev, dy_dev, home_dev = hz.to_device(xb, c.dtype), hz.to_device(dyb, c.dtype), i32(torch, home)
+    if repeats > 1:
+        x_dev, dy_dev = x_dev.repeat(repeats, 1), dy_dev.repeat(repeats, 1)
     lm.forward_train(desc, x_dev, home_dev, None, W_in_p, W_out_p, b, gb)
     lm.backward(desc, dy_dev, home_dev, None, W_in_tp, W_out_tp, b, gb)
     torch.cuda.synchronize()
@@ -385,6 +407,14 @@ def test_backward_config5_full_size(env):
     gradients, 20 x 80 output tiles per expert in the weight gradients."""
     c = wl.CONFIGS[5]
     run_backward_big(env, c, c.C)
+
+
+def test_backward_element_indices_past_two_to_the_31(env):
+    """Maximum sizes: T*d and K*d beyond 2^31 elements (dy, dx, dout, dsend beyond 2^32 bytes): a block of 32 768
+    tokens repeated 17 times, experts of up to 24 576 rows (96 row tiles per expert in the grouped GEMMs)."""
+    cb = wl.small_config(T=32768, d=4096, E=64, N=8, h=256, clusters=64, zipf=0.3)
+    assert 17 * cb.T * cb.d > 2 ** 31
+    run_backward_big(env, cb, 24576, repeats=17)
 
 
 def test_backward_config3_full_size_large_capacity(env):

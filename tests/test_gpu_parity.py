@@ -676,6 +676,109 @@ def test_config5_full_size_routing_stress(env):
     run_big(env, c, c.C, with_ffn=True)
 
 
+def test_element_indices_past_two_to_the_31(env):
+    """Maximum sizes: T*d and K*d lie beyond 2^31 elements (x, y and the send buffer beyond 2^32 bytes), so an
+    address formed in 32 bits anywhere on the path shows as a wrong row.  The input is one seeded block of 32 768
+    tokens repeated 17 times on the device; what depends on one token alone (gating values, expert, score) must
+    repeat bit for bit, what depends on the whole sequence (counts, losses, positions, slots, the packed buffers)
+    is compared with the oracle run on the repeated sequence, the FFN with the oracle on sampled rows of the
+    chosen segments (first, last and random rows of each), Eq. 1's last step with its definition on every token."""
+    import dataclasses
+    torch, lm, hz = env
+    cb = wl.small_config(T=32768, d=4096, E=64, N=8, h=256, clusters=64, zipf=0.3)
+    R, C = 17, 24576
+    c = dataclasses.replace(cb, T=R * cb.T)
+    assert c.T * c.d > 2 ** 31
+    say(f"[past 2^31] T={c.T} d={c.d} E={c.E} h={c.h} C={C}")
+    t0 = time.time()
+    xb, homeb = wl.hidden_states(cb)
+    home = np.tile(homeb, R)
+    x_dev = hz.to_device(xb, c.dtype).repeat(R, 1)
+    desc = lm.make_desc(c.T, c.d, c.E, c.N, c.h, C, c.dtype)
+    b = lm.alloc_buffers(desc)
+    # gate: the first block against the oracle, every other block against the first
+    poison(b.g)
+    lm.locmoe_gate(desc, x_dev, b.g)
+    torch.cuda.synchronize()
+    gref = orc.gate(xb, c.E)
+    g0 = b.g[:cb.T].cpu().numpy()
+    blk = c.d // c.E
+    assert rel_l2(g0, gref) <= 1e-5
+    assert np.all(np.abs(g0 - gref) <= 1e-5 * np.abs(xb.astype(np.float64)).reshape(cb.T, c.E, blk).sum(axis=2) / blk + 1e-30)
+    assert bool((b.g.view(R, cb.T, c.E) == b.g[:cb.T].unsqueeze(0)).all())
+    g32 = np.tile(gref.astype(np.float32), (R, 1))
+    eid, w = check_route(env, c, desc, b, g32, None, home, None, True, wl.ALPHA, wl.MU)
+    assert np.array_equal(eid.reshape(R, cb.T), np.tile(eid[:cb.T], (R, 1)))
+    # dispatch
+    poison(b.send)
+    lm.locmoe_dispatch(desc, x_dev, i32(torch, eid), None, b.pos, b.slot, b.kept, b.seg_off, b.node_off,
+                       b.buf_expert, b.row_token, b.send, b.ws, b.ws_bytes)
+    torch.cuda.synchronize()
+    s = orc.slots(eid, c.E, C, np.arange(c.E) // (c.E // c.N), c.N)
+    K = int(s["seg_off"][-1])
+    assert K * c.d > 2 ** 31
+    for name in ("pos", "slot", "kept", "seg_off", "node_off", "buf_expert"):
+        assert np.array_equal(getattr(b, name).cpu().numpy(), s[name]), name
+    assert np.array_equal(b.row_token.cpu().numpy()[:K], s["row_token"])
+    assert torch.equal(b.send[:K].view(torch.int16), x_dev[b.row_token[:K].long()].view(torch.int16))
+    assert bool(torch.isnan(b.send[K:]).all())
+    say(f"      gate/route/dispatch ok, K={K} dropped={c.T - K} ({time.time() - t0:.1f}s)")
+    # expert FFN: sampled rows of the chosen segments (always the first and the last rows of each)
+    ranks = experts_to_check(s)
+    cand = {int(s["buf_expert"][r]) for r in ranks}
+    W_in, W_out, host_w = hz.upload_weights(c, keep=cand)
+    rng = np.random.default_rng(11)
+    rows_of, ref_of = {}, {}
+    for r in ranks:
+        a, z = int(s["seg_off"][r]), int(s["seg_off"][r + 1])
+        pick = np.unique(np.concatenate([np.arange(a, min(a + 48, z)), np.arange(max(z - 48, a), z),
+                                         rng.integers(a, z, size=160)]))
+        rows_of[r] = pick
+        ref_of[r] = orc.ffn_rows(xb[s["row_token"][pick] % cb.T], *host_w[int(s["buf_expert"][r])])
+
+    def sampled(out_t, H_t, what):
+        assert_rows_written(out_t, K, what + " out"); assert_rows_written(H_t, K, what + " H")
+        for r in ranks:
+            got = hz.to_host_f32(out_t[torch.from_numpy(rows_of[r]).cuda()]).astype(np.float64)
+            diff = np.linalg.norm(got - ref_of[r], axis=1)
+            assert np.all(diff <= 3e-2 * np.linalg.norm(ref_of[r], axis=1) + 1e-30), (what, r)
+            assert rel_l2(got, ref_of[r]) <= 1e-2, (what, r)
+
+    poison(b.out, b.H)
+    lm.locmoe_expert_ffn(desc, b.send, b.seg_off, b.buf_expert, W_in, W_out, b.H, b.out)
+    torch.cuda.synchronize()
+    sampled(b.out, b.H, "row-major weights")
+    out_rm = b.out[:K].clone()
+    dp = packed_desc(lm, desc)
+    assert dp is not None
+    Wi, Wo = pack(env, desc, W_in, W_out)
+    poison(b.out, b.H)
+    lm.locmoe_expert_ffn_ws(dp, b.send, b.seg_off, b.buf_expert, Wi, Wo, b.H, b.out, b.ffn_ws, lm.LOCMOE_FFN_WS_BYTES)
+    torch.cuda.synchronize()
+    sampled(b.out, b.H, "packed weights")
+    # every row: the two kernels, which share neither tiling nor scheduling, agree within the bar
+    for a in range(0, K, 65536):
+        z = min(K, a + 65536)
+        ref = out_rm[a:z].float()
+        diff = (b.out[a:z].float() - ref).norm(dim=1)
+        assert bool((diff <= 3e-2 * ref.norm(dim=1) + 1e-30).all()), a
+    del out_rm
+    say(f"      FFN on {sum(len(v) for v in rows_of.values())} sampled rows of {len(ranks)} segments ok ({time.time() - t0:.1f}s)")
+    # combine: a kept token's row is its score times its out row, rounded once; a dropped token's row is zero
+    poison(b.y)
+    lm.locmoe_combine(dp, b.out, b.slot, b.w, b.y)
+    torch.cuda.synchronize()
+    kept_dev = b.slot >= 0
+    assert not bool(torch.isnan(b.y).any())
+    if bool((~kept_dev).any()):
+        assert float(b.y[~kept_dev].abs().max()) == 0.0
+    for a in range(0, c.T, 131072):
+        idx = torch.nonzero(kept_dev[a:a + 131072]).squeeze(1) + a
+        prod = (b.w[idx][:, None] * b.out[b.slot[idx].long()].float()).to(b.y.dtype)
+        assert torch.equal(b.y[idx], prod), a
+    say(f"      combine ok ({time.time() - t0:.1f}s)")
+
+
 def test_config4_full_size_angles(env):
     """The headline shape: every token's cosine, the histograms and delta_hat against the oracle."""
     angles_case(env, wl.CONFIGS[4], 1, 64)
