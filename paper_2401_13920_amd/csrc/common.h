@@ -125,6 +125,23 @@ __device__ __forceinline__ void dma_1k(const void* sbase, uint32_t voff, uint32_
                "s"(lds_base)
                : "memory", "m0");
 }
+// The same copy in two parts, for runs of copies whose LDS destinations lie within 4 KiB of a common base: M0 is
+// written once (dma_base) and each copy adds an immediate offset of sub KiB (dma_1k_sub).  The hardware adds the
+// immediate to the LDS address and to the global address alike (M0 + imm + 16 l and sbase + voff + imm), so
+// callers whose source does not advance in step with the destination take it off voff.  Nothing else in the
+// calling loop may write M0 between the two parts (the compiler only does so for instructions these kernels do
+// not use; their listings are checked).
+__device__ __forceinline__ void dma_base(uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ void dma_1k_sub(const void* sbase, uint32_t voff, int sub) {
+  switch (sub) {
+    case 0: asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase) : "memory"); break;
+    case 1: asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(voff), "s"(sbase) : "memory"); break;
+    case 2: asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" ::"v"(voff), "s"(sbase) : "memory"); break;
+    default: asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" ::"v"(voff), "s"(sbase) : "memory"); break;
+  }
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");

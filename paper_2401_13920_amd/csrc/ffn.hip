@@ -351,10 +351,14 @@ struct DmaLane {
   uint32_t row0;       // row of this lane in the wave's first block
   uint32_t chunk16;    // byte offset of its source chunk inside a 128-byte row segment
   uint32_t row_bytes;  // bytes per activation row
+  uint32_t row0q;      // the K loop's assignment of blocks to waves: row of this lane in block 4 wave
+  uint32_t chunk16q;   // ... and its source chunk there (blocks 4 wave + odd: chunk16q ^ 64)
 };
 __device__ __forceinline__ DmaLane make_lane(int Kdim, int wave, int lane) {
   const uint32_t row0 = 8 * wave + (lane >> 3);
-  return DmaLane{row0, (uint32_t)(((lane & 7) ^ ((row0 >> 1) & 7)) * 16), (uint32_t)Kdim * 2u};
+  const uint32_t row0q = 32 * wave + (lane >> 3);
+  return DmaLane{row0, (uint32_t)(((lane & 7) ^ ((row0 >> 1) & 7)) * 16), (uint32_t)Kdim * 2u, row0q,
+                 (uint32_t)(((lane & 7) ^ ((row0q >> 1) & 7)) * 16)};
 }
 
 // `span` = rows per m-tile of this segment (at most 256; the segment's last tile may hold fewer)
@@ -392,6 +396,25 @@ __device__ __forceinline__ void issue_a1(const DmaTile& t, const DmaLane& ln, in
   const uint32_t row = min(ln.row0 + 32u * j, (uint32_t)t.rows_left - 1u);
   dma_1k(t.Abase + (size_t)D * (kDmaBK * 4), row * ln.row_bytes + ln.chunk16,
          lds0 + (uint32_t)slot * kASlotBytes + (wave + kDmaWaves * j) * 1024);
+}
+
+// The K loop's copies.  There a wave owns blocks 16 g + 4 wave + sub (g = 0, 1; sub = 0..3) of a slot instead of
+// blocks wave + 4 i: the four blocks of a group are consecutive KiB of LDS, so one M0 write serves four copies
+// (the loop has one wave per SIMD and issues in order: every instruction between two MFMAs costs MFMA time).
+// c = 4 g + sub.  For the weights source and destination advance together; for the activations the immediate is
+// taken off the lane's offset again (from a base 4 KiB below the rows, so that the offset stays non-negative).
+__device__ __forceinline__ void issue_w1q(const char* wbase, int D, int slot, int c, uint32_t lds0, int wave, int lane) {
+  const uint32_t grp = (uint32_t)(c >> 2) * 16384u + (uint32_t)wave * 4096u;
+  if ((c & 3) == 0) dma_base(lds0 + kWRing + (uint32_t)slot * kWSlotBytes + grp);
+  dma_1k_sub(wbase + (size_t)D * kWSlotBytes, grp + lane * 16, c & 3);
+}
+__device__ __forceinline__ void issue_a1q(const DmaTile& t, const DmaLane& ln, int D, int slot, int c, uint32_t lds0,
+                                          int wave) {
+  const uint32_t sub = (uint32_t)(c & 3);
+  if (sub == 0) dma_base(lds0 + (uint32_t)slot * kASlotBytes + (uint32_t)(c >> 2) * 16384u + (uint32_t)wave * 4096u);
+  const uint32_t row = min(ln.row0q + 128u * (uint32_t)(c >> 2) + 8u * sub, (uint32_t)t.rows_left - 1u);
+  dma_1k_sub(t.Abase + (size_t)D * (kDmaBK * 4) - 4096, row * ln.row_bytes + (ln.chunk16q ^ ((sub & 1u) << 6)) + 4096u - sub * 1024u,
+             (int)sub);
 }
 
 // Fills the pipeline for the first tile of a work-group: A(0) W(0) W(1) A(1), all landed and visible to
@@ -502,8 +525,8 @@ __device__ __forceinline__ void dma_tile(const DmaTile& cur, const DmaTile& nxt,
     for (int i = 0; i < NITEM; ++i) {
       if (i < 8) fw[NPAR][i] = read_w(NPAR, i, rslot_w);
       else if (i < NREAD) fa_lo[i - 8] = read_a(NPAR, i - 8, rslot_a);
-      else if (PAR == 0) issue_w1(wsrc, Dsrc, wslot2, i - NREAD, lds0, wave, lane);
-      else issue_a1(over ? nxt : cur, ln, Dsrc, acur, i - NREAD, lds0, wave);
+      else if (PAR == 0) issue_w1q(wsrc, Dsrc, wslot2, i - NREAD, lds0, wave, lane);
+      else issue_a1q(over ? nxt : cur, ln, Dsrc, acur, i - NREAD, lds0, wave);
 #pragma unroll
       for (int q = i * NM / NITEM; q < (i + 1) * NM / NITEM; ++q)
         mfma16_acc<false>(acc[q & 7][4 + (q >> 3)], fw[PAR][q & 7], fa_hi[q >> 3]);

@@ -40,6 +40,10 @@ def test_no_accumulator_read_between_the_last_mfma_and_the_wait_states(tmp_path)
                 if reads.match(lines[j]):
                     bad += 1
                 j -= 1
+    # M0 carries the LDS base of the direct-to-LDS copies across several instructions: the only lines that name
+    # it are the kernels' own writes
+    named = [ln for ln in lines if re.search(r"\bm0\b", ln) and not ln.startswith(";")]
+    assert named and all(ln.startswith("s_mov_b32 m0,") for ln in named), [ln for ln in named if not ln.startswith("s_mov_b32 m0,")][:5]
     # eight row-count variants of the K loop in each of the four epilogue forms of the persistent kernel and of the
     # one-tile-per-group kernel
     assert pairs >= 32, pairs
