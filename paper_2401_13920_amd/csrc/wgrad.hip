@@ -171,23 +171,34 @@ __global__ __launch_bounds__(kWgThreads) void wgrad_dma_kernel(
   const int qrow = lane >> 5, qch = lane & 31;                  // Q copies
   const uint32_t ldP = (uint32_t)Mdim * 2, ldQ = (uint32_t)Ndim * 2;
   const int swz_hi = (wave & 1) << 2;  // bit 3 of the rows this wave copies (rows 8 wave .. 8 wave + 7)
+  // What a copy's source offset is made of, per lane and copy, computed once: the row's byte offset inside a step
+  // and the (swizzled) chunk.  A step then costs an add, a min (rows past the segment's end re-read its last row)
+  // and an add per copy instead of a multiplication and the swizzle arithmetic: with one wave per SIMD every
+  // instruction between two MFMAs is MFMA time (the copies' address arithmetic was 1.1 ms of the 8.3 ms of both
+  // GEMMs at config 4).  The four copies of an operand land in consecutive KiB of LDS: one M0 write serves them,
+  // each copy carries its KiB as immediate offset, which the hardware also adds to the source address; it is taken
+  // off the chunk term again (from a base 4 KiB below the operand, so that the offset stays non-negative).
+  static_assert(S::kPCopies == 4 && S::kPRowsPerCopy == 2, "the copy tables assume 512-byte P rows");
+  uint32_t rowP[4], chP[4], rowQ[4], chQ[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r8p = 2 * q + prow, r8q = 2 * q + qrow;  // row inside the wave's eight
+    rowP[q] = (uint32_t)(8 * wave + r8p) * ldP;
+    chP[q] = (uint32_t)(pch ^ (((r8p & 3) | swz_hi) << 1)) * 16 + 4096 - q * 1024;
+    rowQ[q] = (uint32_t)(8 * wave + r8q) * ldQ;
+    chQ[q] = (uint32_t)(qch ^ (((r8q & 3) | swz_hi) << 1)) * 16 + 4096 - q * 1024;
+  }
   auto issue = [&]() -> bool {
     if (!pf_live) return false;
     const uint32_t sbase = lds0 + (uint32_t)stage_pf * S::kStage;
+    const uint32_t kP = (uint32_t)k_pf * ldP, kQ = (uint32_t)k_pf * ldQ;                     // this step's first row
+    const uint32_t endP = (uint32_t)(pf.rows - 1) * ldP, endQ = (uint32_t)(pf.rows - 1) * ldQ;  // the segment's last row
+    dma_base(sbase + (uint32_t)wave * 8 * S::kPRow);
 #pragma unroll
-    for (int q = 0; q < S::kPCopies; ++q) {
-      const int r8 = S::kPRowsPerCopy * q + prow;         // row inside the wave's eight
-      const int kc = min(k_pf + 8 * wave + r8, pf.rows - 1);  // clamped: always a row of this segment
-      const uint32_t chunk = (uint32_t)(pch ^ (((r8 & 3) | swz_hi) << 1));
-      dma_1k(pf.P, (uint32_t)kc * ldP + chunk * 16, sbase + (uint32_t)wave * 8 * S::kPRow + q * 1024);
-    }
+    for (int q = 0; q < 4; ++q) dma_1k_sub(pf.P - 4096, min(rowP[q] + kP, endP) + chP[q], q);
+    dma_base(sbase + S::kPBytes + (uint32_t)wave * 4096);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r8 = 2 * q + qrow;
-      const int kc = min(k_pf + 8 * wave + r8, pf.rows - 1);
-      const uint32_t chunk = (uint32_t)(qch ^ (((r8 & 3) | swz_hi) << 1));
-      dma_1k(pf.Q, (uint32_t)kc * ldQ + chunk * 16, sbase + S::kPBytes + (uint32_t)wave * 4096 + q * 1024);
-    }
+    for (int q = 0; q < 4; ++q) dma_1k_sub(pf.Q - 4096, min(rowQ[q] + kQ, endQ) + chQ[q], q);
     stage_pf = stage_pf + 1 == S::kStages ? 0 : stage_pf + 1;
     k_pf += kWgK;
     if (k_pf >= pf.rows) {
